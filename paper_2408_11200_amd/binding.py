@@ -1,0 +1,238 @@
+"""ctypes front end of libkan_hip.so: same entry-point names as include/kan.h.
+
+Argument marshalling only.  PyTorch is used to hold device memory and to name
+the stream; every step of the layer runs inside the HIP library.  If the
+library has not been built the first call raises: there is no fallback.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkan_hip.so")
+
+KAN_OK = 0
+KAN_ERR_INVALID_ARG = -1
+KAN_ERR_UNSUPPORTED = -2
+KAN_ERR_WORKSPACE = -3
+KAN_ERR_RANGE = -4
+KAN_ERR_HIP = -5
+PASS_FORWARD, PASS_BACKWARD = 0, 1
+
+EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
+           "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_group_index"]
+
+
+class KanLayerDesc(ctypes.Structure):
+    _fields_ = [("n_in", ctypes.c_int32), ("n_out", ctypes.c_int32), ("G", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("grid_lo", ctypes.c_float), ("grid_hi", ctypes.c_float),
+                ("base_act", ctypes.c_int32)]
+
+
+class UkanLayerDesc(ctypes.Structure):
+    _fields_ = [("n_in", ctypes.c_int32), ("n_out", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("h", ctypes.c_float), ("d_pe", ctypes.c_int32), ("d_feat", ctypes.c_int32),
+                ("d_hidden", ctypes.c_int32), ("base_act", ctypes.c_int32)]
+
+
+class UkanParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("E", "W1", "b1", "W2", "b2", "scale", "w_b")]
+
+
+class UkanGrads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("gE", "gW1", "gb1", "gW2", "gb2", "gscale", "gw_b")]
+
+
+class KanError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+_lib = None
+
+
+def load():
+    """Load the built library; raise if it is missing (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s is missing: build it with `python -m paper_2408_11200_amd.build`" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, sz, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int32
+    lib.kan_strerror.restype = ctypes.c_char_p
+    lib.kan_strerror.argtypes = [ctypes.c_int]
+    lib.kan_workspace_bytes.restype = sz
+    lib.kan_workspace_bytes.argtypes = [ctypes.POINTER(KanLayerDesc), i64, ctypes.c_int]
+    lib.kan_forward.restype = ctypes.c_int
+    lib.kan_forward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kan_backward.restype = ctypes.c_int
+    lib.kan_backward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kan_interval_index.restype = ctypes.c_int
+    lib.kan_interval_index.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp]
+    lib.ukan_workspace_bytes.restype = sz
+    lib.ukan_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i32, ctypes.c_int]
+    lib.ukan_cg_forward.restype = ctypes.c_int
+    lib.ukan_cg_forward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, i32,
+                                    vp, sz, vp]
+    lib.ukan_cg_backward.restype = ctypes.c_int
+    lib.ukan_cg_backward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, vp,
+                                     ctypes.POINTER(UkanGrads), i32, vp, sz, vp]
+    lib.ukan_group_index.restype = ctypes.c_int
+    lib.ukan_group_index.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def strerror(status):
+    return load().kan_strerror(int(status)).decode()
+
+
+def kan_desc(spec):
+    """KanLayerDesc from anything with n_in, n_out, G, k, grid_lo, grid_hi, base_act."""
+    return KanLayerDesc(spec.n_in, spec.n_out, spec.G, spec.k, spec.grid_lo, spec.grid_hi, spec.base_act)
+
+
+def ukan_desc(spec):
+    return UkanLayerDesc(spec.n_in, spec.n_out, spec.k, spec.h, spec.d_pe, spec.d_feat, spec.d_hidden,
+                         spec.base_act)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _f32(t):
+    assert t is None or t.dtype == torch.float32
+    return _ptr(t)
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(nbytes, device):
+    # torch's allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def kan_workspace_bytes(spec, B, which=PASS_FORWARD):
+    d = kan_desc(spec)
+    return int(load().kan_workspace_bytes(ctypes.byref(d), B, which))
+
+
+def kan_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=None):
+    lib = load()
+    d = kan_desc(spec)
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_FORWARD), x.device)
+    rc = lib.kan_forward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(y),
+                         _ptr(ws), ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_forward")
+    return y
+
+
+def kan_backward(spec, x, coef, w_s, w_b, gy, want=("gx", "gcoef", "gw_s", "gw_b"), out=None, ws=None,
+                 stream=None):
+    lib = load()
+    d = kan_desc(spec)
+    B = x.shape[0]
+    shapes = {"gx": (B, spec.n_in), "gcoef": (spec.n_in, spec.G + spec.k, spec.n_out),
+              "gw_s": (spec.n_in, spec.n_out), "gw_b": (spec.n_in, spec.n_out)}
+    out = dict(out or {})
+    for name in want:
+        if name not in out:
+            out[name] = torch.empty(shapes[name], dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_BACKWARD), x.device)
+    rc = lib.kan_backward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
+                          _f32(out.get("gx")), _f32(out.get("gcoef")), _f32(out.get("gw_s")),
+                          _f32(out.get("gw_b")), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_backward")
+    return out
+
+
+def kan_interval_index(spec, x, stream=None):
+    lib = load()
+    d = kan_desc(spec)
+    idx = torch.empty(x.shape, dtype=torch.int32, device=x.device)
+    rc = lib.kan_interval_index(ctypes.byref(d), x.numel(), _f32(x), _ptr(idx), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_interval_index")
+    return idx
+
+
+# ------------------------------------------------------------------ UKAN ----
+
+_P_NAMES = ("E", "W1", "b1", "W2", "b2", "scale", "w_b")
+
+
+def _ukan_params(p):
+    return UkanParams(*[(_f32(p.get(n)).value if p.get(n) is not None else None) for n in _P_NAMES])
+
+
+def ukan_workspace_bytes(spec, B, max_groups, which=PASS_FORWARD):
+    d = ukan_desc(spec)
+    return int(load().ukan_workspace_bytes(ctypes.byref(d), B, max_groups, which))
+
+
+def ukan_cg_forward(spec, x, p, max_groups, y=None, ws=None, stream=None):
+    lib = load()
+    d = ukan_desc(spec)
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_FORWARD), x.device)
+    pp = _ukan_params(p)
+    rc = lib.ukan_cg_forward(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(y), max_groups, _ptr(ws),
+                             ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "ukan_cg_forward")
+    return y
+
+
+def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, ws=None, stream=None):
+    lib = load()
+    d = ukan_desc(spec)
+    B = x.shape[0]
+    K = spec.k + 1
+    shapes = {"gx": (B, spec.n_in), "gE": (spec.n_in, spec.d_feat),
+              "gW1": (spec.d_feat + spec.d_pe, spec.d_hidden), "gb1": (spec.d_hidden,),
+              "gW2": (spec.d_hidden, K * spec.n_out), "gb2": (K * spec.n_out,),
+              "gscale": (spec.n_in, spec.n_out), "gw_b": (spec.n_in, spec.n_out)}
+    if want is None:
+        want = [n for n in shapes if n != "gw_b" or spec.base_act]
+    out = {n: torch.empty(shapes[n], dtype=torch.float32, device=x.device) for n in want}
+    if ws is None:
+        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_BACKWARD), x.device)
+    pp = _ukan_params(p)
+    gg = UkanGrads(*[(out[n].data_ptr() if n in out else None)
+                     for n in ("gE", "gW1", "gb1", "gW2", "gb2", "gscale", "gw_b")])
+    rc = lib.ukan_cg_backward(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(gy), _f32(out.get("gx")),
+                              ctypes.byref(gg), max_groups, _ptr(ws), ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "ukan_cg_backward")
+    return out
+
+
+def ukan_group_index(spec, x, stream=None):
+    lib = load()
+    d = ukan_desc(spec)
+    outs = [torch.empty(x.shape, dtype=torch.int32, device=x.device) for _ in range(3)]
+    rc = lib.ukan_group_index(ctypes.byref(d), x.numel(), _f32(x), _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]),
+                              _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "ukan_group_index")
+    return tuple(outs)

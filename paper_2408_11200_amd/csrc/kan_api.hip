@@ -1,0 +1,138 @@
+// C ABI of the bounded-grid KAN layer: argument checks, workspace layout and
+// kernel dispatch.  See include/kan.h for the contract.
+#include "kan.h"
+#include "kan_launch.hpp"
+
+using namespace kan;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int check_desc(const kan_layer_desc *d)
+{
+    if (!d) return KAN_ERR_INVALID_ARG;
+    if (d->n_in <= 0 || d->n_out <= 0 || d->G <= 0) return KAN_ERR_INVALID_ARG;
+    if (!(d->grid_hi > d->grid_lo)) return KAN_ERR_INVALID_ARG;
+    if (d->k < 1 || d->k > 3) return KAN_ERR_UNSUPPORTED;
+    if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
+    return KAN_OK;
+}
+
+SplineGeom geom_of(const kan_layer_desc *d)
+{
+    SplineGeom g;
+    g.n_in = d->n_in;
+    g.n_out = d->n_out;
+    g.rows = d->G + d->k;
+    g.k = d->k;
+    g.lo = d->grid_lo;
+    g.inv_h = (float)d->G / (d->grid_hi - d->grid_lo);
+    g.cell_base = nullptr;
+    g.base_act = d->base_act;
+    return g;
+}
+
+size_t folded_bytes(const kan_layer_desc *d)
+{
+    return align_up((size_t)d->n_in * (size_t)(d->G + d->k) * (size_t)d->n_out * sizeof(float));
+}
+
+size_t edge_bytes(const kan_layer_desc *d)
+{
+    return align_up((size_t)d->n_in * (size_t)d->n_out * sizeof(float));
+}
+
+}  // namespace
+
+extern "C" const char *kan_strerror(int status)
+{
+    switch (status) {
+    case KAN_OK: return "ok";
+    case KAN_ERR_INVALID_ARG: return "invalid argument";
+    case KAN_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KAN_ERR_RANGE: return "input spans more groups than max_groups";
+    case KAN_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+extern "C" size_t kan_workspace_bytes(const kan_layer_desc *desc, int64_t B, int pass)
+{
+    if (check_desc(desc) != KAN_OK || B < 0) return 0;
+    if (pass == KAN_PASS_FORWARD) return folded_bytes(desc);
+    if (pass != KAN_PASS_BACKWARD) return 0;
+    ChunkPlan cp = plan_chunks(B, desc->n_in, desc->G + desc->k, desc->n_out);
+    return folded_bytes(desc) + (size_t)cp.n_chunks * (folded_bytes(desc) + edge_bytes(desc));
+}
+
+extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                           const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
+                           void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != KAN_OK) return rc;
+    if (B < 0) return KAN_ERR_INVALID_ARG;
+    if (B == 0) return KAN_OK;
+    if (!x || !coef || !w_s || !y) return KAN_ERR_INVALID_ARG;
+    if (desc->base_act != KAN_BASE_NONE && !w_b) return KAN_ERR_INVALID_ARG;
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < kan_workspace_bytes(desc, B, KAN_PASS_FORWARD))
+        return KAN_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    SplineGeom g = geom_of(desc);
+    float *cf = (float *)ws;
+    if (launch_fold_scale(coef, w_s, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
+    if (launch_forward_generic(g, x, cf, w_b, y, B, st) != hipSuccess) return KAN_ERR_HIP;
+    return KAN_OK;
+}
+
+extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                            const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
+                            float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != KAN_OK) return rc;
+    if (B < 0) return KAN_ERR_INVALID_ARG;
+    if (B == 0) return KAN_OK;
+    if (!x || !coef || !w_s || !gy) return KAN_ERR_INVALID_ARG;
+    if (desc->base_act != KAN_BASE_NONE && !w_b) return KAN_ERR_INVALID_ARG;
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < kan_workspace_bytes(desc, B, KAN_PASS_BACKWARD))
+        return KAN_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    SplineGeom g = geom_of(desc);
+    if (!dparam_generic_supported(g.rows) && (gcoef || gw_s || gw_b)) return KAN_ERR_UNSUPPORTED;
+    float *cf = (float *)ws;
+    if (gx) {
+        if (launch_fold_scale(coef, w_s, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
+        if (launch_dx_generic(g, x, cf, w_b, gy, gx, B, st) != hipSuccess) return KAN_ERR_HIP;
+    }
+    const bool want_b = gw_b && desc->base_act != KAN_BASE_NONE;
+    if (gcoef || gw_s || gw_b) {
+        ChunkPlan cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
+        float *part_c = (float *)((char *)ws + folded_bytes(desc));
+        float *part_b = (float *)((char *)part_c + (size_t)cp.n_chunks * folded_bytes(desc));
+        // partial slabs are laid out back to back with the unpadded slab size
+        if (launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
+                                  st) != hipSuccess)
+            return KAN_ERR_HIP;
+        if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
+                                 g.n_out, cp.n_chunks, st) != hipSuccess)
+            return KAN_ERR_HIP;
+    }
+    return KAN_OK;
+}
+
+extern "C" int kan_interval_index(const kan_layer_desc *desc, int64_t n, const float *x, int32_t *idx,
+                                  void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != KAN_OK) return rc;
+    if (n < 0) return KAN_ERR_INVALID_ARG;
+    if (n == 0) return KAN_OK;
+    if (!x || !idx) return KAN_ERR_INVALID_ARG;
+    SplineGeom g = geom_of(desc);
+    if (launch_interval_index(x, idx, n, g.lo, g.inv_h, (hipStream_t)stream) != hipSuccess) return KAN_ERR_HIP;
+    return KAN_OK;
+}

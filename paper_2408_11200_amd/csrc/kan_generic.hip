@@ -1,0 +1,466 @@
+// Generic kernels of the local B-spline layer: they work for every shape the
+// library accepts (any n_in, n_out, grid size, k <= 3, per-input cell offsets)
+// and are the fallback when no specialised kernel applies.
+//
+// Common mapping: lanes <-> outputs.  One wave owns T samples and a tile of
+// 64*R outputs; the per-(sample, input) quantities (cell, window weights, base
+// value) are wave-uniform, evaluated 64 pairs at a time with one pair per lane
+// and then broadcast lane by lane into scalar registers, so the per-edge work is
+// K multiply-adds whose coefficient operands are unit-stride across lanes.
+#include "kan_device.hpp"
+#include "kan_launch.hpp"
+
+namespace kan {
+
+// ---- helpers --------------------------------------------------------------
+
+template <int R> struct VecOf;
+template <> struct VecOf<1> { using type = float; };
+template <> struct VecOf<2> { using type = float2; };
+template <> struct VecOf<4> { using type = float4; };
+
+template <int R>
+__device__ __forceinline__ void load_vec(const float *p, float (&v)[R])
+{
+    if constexpr (R == 1) {
+        v[0] = *p;
+    } else if constexpr (R == 2) {
+        float2 t = *reinterpret_cast<const float2 *>(p);
+        v[0] = t.x; v[1] = t.y;
+    } else {
+        float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+}
+
+template <int R>
+__device__ __forceinline__ void store_vec(float *p, const float (&v)[R])
+{
+    if constexpr (R == 1) {
+        *p = v[0];
+    } else if constexpr (R == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+    } else {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+// ---- interval index export --------------------------------------------------
+
+__global__ void interval_index_kernel(const float *__restrict__ x, int32_t *__restrict__ idx, int64_t n,
+                                      float lo, float inv_h)
+{
+    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n) {
+        float t, d;
+        idx[p] = interval_index(x[p], lo, inv_h, &t, &d);
+    }
+}
+
+// ---- fold the per-edge spline scale into the coefficients -------------------
+// cf[i][m][j] = w_s[i][j] * coef[i][m][j]; afterwards the spline term costs K
+// multiply-adds per edge with no separate scale.
+__global__ void fold_scale_kernel(const float *__restrict__ coef, const float *__restrict__ w_s,
+                                  float *__restrict__ cf, int n_in, int rows, int n_out)
+{
+    int64_t total = (int64_t)n_in * rows * n_out;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total;
+         p += (int64_t)gridDim.x * blockDim.x) {
+        int j = (int)(p % n_out);
+        int i = (int)(p / ((int64_t)rows * n_out));
+        cf[p] = coef[p] * w_s[(int64_t)i * n_out + j];
+    }
+}
+
+// ---- forward ---------------------------------------------------------------
+// grid.x = batch tiles of 4*T samples, grid.y = output tiles of 64*R.
+template <int R, int T>
+__global__ __launch_bounds__(256) void forward_generic_kernel(SplineGeom g, const float *__restrict__ x,
+                                                              const float *__restrict__ cf,
+                                                              const float *__restrict__ w_b,
+                                                              float *__restrict__ y, int64_t B)
+{
+    constexpr int IPV = kWave / T;      // inputs covered by one vector evaluation
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t b0 = ((int64_t)blockIdx.x * 4 + wave) * T;
+    if (b0 >= B) return;                // whole wave out of range (uniform)
+    const int j = blockIdx.y * (kWave * R) + lane * R;
+    const bool j_ok = j < g.n_out;      // n_out is a multiple of R
+    const int jc = j_ok ? j : 0;
+
+    float acc[T][R];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[t][r] = 0.0f;
+
+    const int my_t = lane % T, my_ii = lane / T;
+    const int64_t my_b = (b0 + my_t < B) ? b0 + my_t : B - 1;
+
+    for (int i0 = 0; i0 < g.n_in; i0 += IPV) {
+        const int my_i = i0 + my_ii;
+        const bool i_ok = my_i < g.n_in;
+        const int ic = i_ok ? my_i : g.n_in - 1;
+        Pair p = pair_eval<false>(x[my_b * g.n_in + ic], g, ic);
+        if (!i_ok) { p.cell = -kMaxK; p.base = 0.0f; }
+
+        const int n_ii = (g.n_in - i0 < IPV) ? g.n_in - i0 : IPV;
+        for (int ii = 0; ii < n_ii; ++ii) {
+            const float *slab = cf + (int64_t)(i0 + ii) * g.rows * g.n_out + jc;
+            float wb[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) wb[r] = 0.0f;
+            if (g.base_act) load_vec<R>(w_b + (int64_t)(i0 + ii) * g.n_out + jc, wb);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int src = ii * T + t;
+                const int cell = lane_i(p.cell, src);
+                if (cell > -kMaxK && cell < g.rows) {       // uniform: some weight is non-zero
+                    float c[kMaxK][R];
+#pragma unroll
+                    for (int s = 0; s < kMaxK; ++s)
+                        load_vec<R>(slab + (int64_t)clampi(cell + s, 0, g.rows - 1) * g.n_out, c[s]);
+#pragma unroll
+                    for (int s = 0; s < kMaxK; ++s) {
+                        const float ws = lane_f(p.w[s], src);
+#pragma unroll
+                        for (int r = 0; r < R; ++r) acc[t][r] = fmaf(ws, c[s][r], acc[t][r]);
+                    }
+                }
+                if (g.base_act) {
+                    const float bs = lane_f(p.base, src);
+#pragma unroll
+                    for (int r = 0; r < R; ++r) acc[t][r] = fmaf(bs, wb[r], acc[t][r]);
+                }
+            }
+        }
+    }
+    if (j_ok) {
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+            if (b0 + t < B) store_vec<R>(y + (b0 + t) * g.n_out + j, acc[t]);
+    }
+}
+
+// ---- backward: dL/dx ---------------------------------------------------------
+// One wave owns T samples and walks over every output tile; per pair it forms the
+// per-lane partial  q = sum_r gy_r * (sum_s dw_s * cf_s[r] + dbase * w_b[r])  and the
+// 64 partial vectors of one evaluation round are reduced together by a butterfly
+// that ends with lane p holding the total of pair p, which is the lane that
+// evaluated the pair and now stores gx for it.
+template <int N>
+__device__ __forceinline__ void butterfly_step(float (&q)[kWave], int lane)
+{
+    // q[0..2N) -> q[0..N): lanes with bit N clear keep the low half, the others the high half
+    const bool up = (lane & N) != 0;
+#pragma unroll
+    for (int m = 0; m < N; ++m) {
+        float keep = up ? q[m + N] : q[m];
+        float send = up ? q[m] : q[m + N];
+        q[m] = keep + __shfl_xor(send, N, kWave);
+    }
+}
+
+template <int R, int T>
+__global__ __launch_bounds__(256) void dx_generic_kernel(SplineGeom g, const float *__restrict__ x,
+                                                         const float *__restrict__ cf,
+                                                         const float *__restrict__ w_b,
+                                                         const float *__restrict__ gy,
+                                                         float *__restrict__ gx, int64_t B)
+{
+    constexpr int IPV = kWave / T;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t b0 = ((int64_t)blockIdx.x * 4 + wave) * T;
+    if (b0 >= B) return;
+    const int my_t = lane % T, my_ii = lane / T;
+    const int64_t my_b = (b0 + my_t < B) ? b0 + my_t : B - 1;
+    const int n_jt = (g.n_out + kWave * R - 1) / (kWave * R);
+
+    for (int i0 = 0; i0 < g.n_in; i0 += IPV) {
+        const int my_i = i0 + my_ii;
+        const bool i_ok = my_i < g.n_in;
+        const int ic = i_ok ? my_i : g.n_in - 1;
+        Pair p = pair_eval<true>(x[my_b * g.n_in + ic], g, ic);
+        if (!i_ok) { p.cell = -kMaxK; p.dbase = 0.0f; }
+
+        float q[kWave];
+#pragma unroll
+        for (int m = 0; m < kWave; ++m) q[m] = 0.0f;
+
+        for (int jt = 0; jt < n_jt; ++jt) {
+            const int j = jt * (kWave * R) + lane * R;
+            const bool j_ok = j < g.n_out;
+            const int jc = j_ok ? j : 0;
+            float gyv[T][R];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int64_t b = (b0 + t < B) ? b0 + t : B - 1;
+                load_vec<R>(gy + b * g.n_out + jc, gyv[t]);
+                if (!j_ok) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) gyv[t][r] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int ii = 0; ii < IPV; ++ii) {
+                if (i0 + ii < g.n_in) {
+                    const float *slab = cf + (int64_t)(i0 + ii) * g.rows * g.n_out + jc;
+                    float wb[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) wb[r] = 0.0f;
+                    if (g.base_act) load_vec<R>(w_b + (int64_t)(i0 + ii) * g.n_out + jc, wb);
+#pragma unroll
+                    for (int t = 0; t < T; ++t) {
+                        const int src = ii * T + t;
+                        const int cell = lane_i(p.cell, src);
+                        float d[R];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) d[r] = 0.0f;
+                        if (cell > -kMaxK && cell < g.rows) {
+                            float c[kMaxK][R];
+#pragma unroll
+                            for (int s = 0; s < kMaxK; ++s)
+                                load_vec<R>(slab + (int64_t)clampi(cell + s, 0, g.rows - 1) * g.n_out, c[s]);
+#pragma unroll
+                            for (int s = 0; s < kMaxK; ++s) {
+                                const float dws = lane_f(p.dw[s], src);
+#pragma unroll
+                                for (int r = 0; r < R; ++r) d[r] = fmaf(dws, c[s][r], d[r]);
+                            }
+                        }
+                        if (g.base_act) {
+                            const float dbs = lane_f(p.dbase, src);
+#pragma unroll
+                            for (int r = 0; r < R; ++r) d[r] = fmaf(dbs, wb[r], d[r]);
+                        }
+#pragma unroll
+                        for (int r = 0; r < R; ++r) q[src] = fmaf(gyv[t][r], d[r], q[src]);
+                    }
+                }
+            }
+        }
+        butterfly_step<32>(q, lane);
+        butterfly_step<16>(q, lane);
+        butterfly_step<8>(q, lane);
+        butterfly_step<4>(q, lane);
+        butterfly_step<2>(q, lane);
+        butterfly_step<1>(q, lane);
+        if (i_ok && b0 + my_t < B) gx[(b0 + my_t) * g.n_in + my_i] = q[0];
+    }
+}
+
+// ---- backward: parameter gradients -------------------------------------------
+// Stage 1.  One wave owns input i, a tile of 64*R outputs and one chunk of the
+// batch, and keeps
+//   acc[m][j] = sum_{b in chunk} gy[b][j] * N_{m - cell(b,i)}(u(b,i))
+// in LDS that only this wave touches; samples are visited in index order, so the
+// sum order is fixed.  The raw sums go to part_c[chunk][i][m][j] and the base-term
+// sums  sum_b gy[b][j] * silu(x[b][i])  to part_b[chunk][i][j].
+template <int R>
+__global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const float *__restrict__ x,
+                                                            const float *__restrict__ gy,
+                                                            float *__restrict__ part_c,
+                                                            float *__restrict__ part_b, int64_t B,
+                                                            int64_t chunk_len)
+{
+    extern __shared__ float acc[];          // [rows][64*R]
+    constexpr int TJ = kWave * R;
+    const int lane = threadIdx.x;
+    const int i = blockIdx.x;
+    const int j = blockIdx.y * TJ + lane * R;
+    const bool j_ok = j < g.n_out;
+    const int jc = j_ok ? j : 0;
+    const int64_t b_lo = (int64_t)blockIdx.z * chunk_len;
+    const int64_t b_hi = (b_lo + chunk_len < B) ? b_lo + chunk_len : B;
+
+    for (int m = 0; m < g.rows; ++m)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[m * TJ + lane * R + r] = 0.0f;
+    float accb[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) accb[r] = 0.0f;
+
+    for (int64_t b0 = b_lo; b0 < b_hi; b0 += kWave) {
+        const int64_t my_b = (b0 + lane < b_hi) ? b0 + lane : b_hi - 1;
+        Pair p = pair_eval<false>(x[my_b * g.n_in + i], g, i);
+        const int n_b = (b_hi - b0 < kWave) ? (int)(b_hi - b0) : kWave;
+        for (int t = 0; t < n_b; ++t) {
+            float gv[R];
+            load_vec<R>(gy + (b0 + t) * g.n_out + jc, gv);
+            const int cell = lane_i(p.cell, t);
+            if (cell > -kMaxK && cell < g.rows) {
+#pragma unroll
+                for (int s = 0; s < kMaxK; ++s) {
+                    const float ws = lane_f(p.w[s], t);
+                    float *row = acc + clampi(cell + s, 0, g.rows - 1) * TJ + lane * R;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) row[r] = fmaf(ws, gv[r], row[r]);
+                }
+            }
+            if (g.base_act) {
+                const float bs = lane_f(p.base, t);
+#pragma unroll
+                for (int r = 0; r < R; ++r) accb[r] = fmaf(bs, gv[r], accb[r]);
+            }
+        }
+    }
+    if (!j_ok) return;
+    float *pc = part_c + ((int64_t)blockIdx.z * g.n_in + i) * g.rows * g.n_out + j;
+    for (int m = 0; m < g.rows; ++m) {
+        float a[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) a[r] = acc[m * TJ + lane * R + r];
+        store_vec<R>(pc + (int64_t)m * g.n_out, a);
+    }
+    if (part_b) store_vec<R>(part_b + ((int64_t)blockIdx.z * g.n_in + i) * g.n_out + j, accb);
+}
+
+// Stage 2.  Sum the per-chunk partial sums in chunk order (fp64 accumulator, so the
+// long batch sum costs no accuracy) and turn them into the three gradients:
+//   gcoef = w_s * acc,   gw_s = sum_m coef * acc,   gw_b = base sums.
+// One thread per (input, output); consecutive threads read consecutive outputs.
+__global__ __launch_bounds__(256) void dparam_reduce_kernel(const float *__restrict__ part_c,
+                                                            const float *__restrict__ part_b,
+                                                            const float *__restrict__ coef,
+                                                            const float *__restrict__ w_s,
+                                                            float *__restrict__ gcoef, float *__restrict__ gw_s,
+                                                            float *__restrict__ gw_b, int n_in, int rows,
+                                                            int n_out, int n_chunks)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)n_in * n_out) return;
+    const int i = (int)(e / n_out), j = (int)(e % n_out);
+    const int64_t slab = (int64_t)n_in * rows * n_out;
+    const float ws = w_s[e];
+    double gws = 0.0;
+    if (gcoef || gw_s) {
+        for (int m = 0; m < rows; ++m) {
+            const int64_t at = ((int64_t)i * rows + m) * n_out + j;
+            double a = 0.0;
+            for (int c = 0; c < n_chunks; ++c) a += (double)part_c[c * slab + at];
+            if (gcoef) gcoef[at] = (float)((double)ws * a);
+            if (gw_s) gws += (double)coef[at] * a;
+        }
+        if (gw_s) gw_s[e] = (float)gws;
+    }
+    if (gw_b) {
+        double a = 0.0;
+        if (part_b)      // no base term: the gradient is identically zero
+            for (int c = 0; c < n_chunks; ++c) a += (double)part_b[(int64_t)c * n_in * n_out + e];
+        gw_b[e] = (float)a;
+    }
+}
+
+// ---- launchers -------------------------------------------------------------
+
+static int pick_r(int n_out)
+{
+    if (n_out % 4 == 0 && n_out >= 256) return 4;
+    if (n_out % 2 == 0 && n_out >= 128) return 2;
+    return 1;
+}
+
+hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float lo, float inv_h,
+                                 hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n + 255) / 256);
+    interval_index_kernel<<<blocks, 256, 0, st>>>(x, idx, n, lo, inv_h);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold_scale(const float *coef, const float *w_s, float *cf, int n_in, int rows, int n_out,
+                             hipStream_t st)
+{
+    int64_t total = (int64_t)n_in * rows * n_out;
+    int64_t want = (total + 255) / 256;
+    unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+    fold_scale_kernel<<<blocks, 256, 0, st>>>(coef, w_s, cf, n_in, rows, n_out);
+    return hipGetLastError();
+}
+
+template <int R>
+static hipError_t forward_r(const SplineGeom &g, const float *x, const float *cf, const float *w_b, float *y,
+                            int64_t B, hipStream_t st)
+{
+    constexpr int T = (R == 4) ? 8 : 16;
+    dim3 grid((unsigned)((B + 4 * T - 1) / (4 * T)), (unsigned)((g.n_out + 64 * R - 1) / (64 * R)));
+    forward_generic_kernel<R, T><<<grid, 256, 0, st>>>(g, x, cf, w_b, y, B);
+    return hipGetLastError();
+}
+
+hipError_t launch_forward_generic(const SplineGeom &g, const float *x, const float *cf, const float *w_b,
+                                  float *y, int64_t B, hipStream_t st)
+{
+    switch (pick_r(g.n_out)) {
+    case 4: return forward_r<4>(g, x, cf, w_b, y, B, st);
+    case 2: return forward_r<2>(g, x, cf, w_b, y, B, st);
+    default: return forward_r<1>(g, x, cf, w_b, y, B, st);
+    }
+}
+
+template <int R>
+static hipError_t dx_r(const SplineGeom &g, const float *x, const float *cf, const float *w_b, const float *gy,
+                       float *gx, int64_t B, hipStream_t st)
+{
+    constexpr int T = 8;
+    dim3 grid((unsigned)((B + 4 * T - 1) / (4 * T)));
+    dx_generic_kernel<R, T><<<grid, 256, 0, st>>>(g, x, cf, w_b, gy, gx, B);
+    return hipGetLastError();
+}
+
+hipError_t launch_dx_generic(const SplineGeom &g, const float *x, const float *cf, const float *w_b,
+                             const float *gy, float *gx, int64_t B, hipStream_t st)
+{
+    switch (pick_r(g.n_out)) {
+    case 4: return dx_r<4>(g, x, cf, w_b, gy, gx, B, st);
+    case 2: return dx_r<2>(g, x, cf, w_b, gy, gx, B, st);
+    default: return dx_r<1>(g, x, cf, w_b, gy, gx, B, st);
+    }
+}
+
+// LDS bytes one dparam wave needs; the launcher lowers R until the tile fits.
+static size_t dparam_lds(int rows, int R) { return (size_t)rows * 64 * R * sizeof(float); }
+
+int dparam_generic_supported(int rows) { return dparam_lds(rows, 1) <= 160 * 1024 ? 1 : 0; }
+
+hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const float *gy, float *part_c,
+                                 float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st)
+{
+    int R = pick_r(g.n_out);
+    while (R > 1 && dparam_lds(g.rows, R) > 48 * 1024) R /= 2;
+    size_t lds = dparam_lds(g.rows, R);
+    dim3 grid((unsigned)g.n_in, (unsigned)((g.n_out + 64 * R - 1) / (64 * R)), (unsigned)n_chunks);
+    hipError_t e = hipSuccess;
+    switch (R) {
+    case 4:
+        dparam_generic_kernel<4><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
+        break;
+    case 2:
+        dparam_generic_kernel<2><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
+        break;
+    default:
+        if (lds > 64 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dparam_generic_kernel<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        dparam_generic_kernel<1><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
+        break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const float *coef, const float *w_s,
+                                float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
+                                int n_chunks, hipStream_t st)
+{
+    int64_t total = (int64_t)n_in * n_out;
+    dparam_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part_c, part_b, coef, w_s, gcoef, gw_s,
+                                                                        gw_b, n_in, rows, n_out, n_chunks);
+    return hipGetLastError();
+}
+
+}  // namespace kan

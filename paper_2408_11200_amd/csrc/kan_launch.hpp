@@ -1,0 +1,47 @@
+// Host-side launch functions of the kernels (one per kernel family).  Each
+// enqueues on the given stream and returns the HIP launch status; none
+// synchronises or allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "kan_device.hpp"
+
+namespace kan {
+
+hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float lo, float inv_h,
+                                 hipStream_t st);
+hipError_t launch_fold_scale(const float *coef, const float *w_s, float *cf, int n_in, int rows, int n_out,
+                             hipStream_t st);
+
+// generic (any shape) kernels
+hipError_t launch_forward_generic(const SplineGeom &g, const float *x, const float *cf, const float *w_b,
+                                  float *y, int64_t B, hipStream_t st);
+hipError_t launch_dx_generic(const SplineGeom &g, const float *x, const float *cf, const float *w_b,
+                             const float *gy, float *gx, int64_t B, hipStream_t st);
+int dparam_generic_supported(int rows);
+hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const float *gy, float *part_c,
+                                 float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
+hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const float *coef, const float *w_s,
+                                float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
+                                int n_chunks, hipStream_t st);
+
+// How the batch is cut into chunks for the parameter-gradient reduction: chunks of about 1024
+// samples, at most 64 of them, and no more than fit a 512 MiB budget of partial sums.
+struct ChunkPlan { int n_chunks; int64_t chunk_len; };
+inline ChunkPlan plan_chunks(int64_t B, int n_in, int rows, int n_out)
+{
+    int64_t slab = (int64_t)n_in * rows * n_out * (int64_t)sizeof(float);
+    int64_t by_budget = (512ll << 20) / (slab > 0 ? slab : 1);
+    int64_t n = (B + 1023) / 1024;
+    if (n > 64) n = 64;
+    if (n > by_budget) n = by_budget;
+    if (n < 1) n = 1;
+    ChunkPlan p;
+    p.chunk_len = (B + n - 1) / n;
+    if (p.chunk_len < 1) p.chunk_len = 1;
+    p.n_chunks = (int)((B + p.chunk_len - 1) / p.chunk_len);
+    if (p.n_chunks < 1) p.n_chunks = 1;
+    return p;
+}
+
+}  // namespace kan

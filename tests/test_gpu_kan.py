@@ -1,0 +1,236 @@
+"""Parity of the HIP KAN layer (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bars: interval indices bit-exact; forward |err| <= 1e-5 (1 + |ref|); gradients
+|err| <= 1e-4 (1 + |ref|), all in fp32 against the fp64 oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2408_11200_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+FWD_TOL = 1e-5
+GRAD_TOL = 1e-4
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def assert_close(got, ref, tol, what):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    bound = tol * (1.0 + np.abs(ref))
+    bad = err > bound
+    assert not bad.any(), "%s: %d/%d outside tolerance, worst err %.3e at ref %.3e (ratio %.2f)" % (
+        what, bad.sum(), bad.size, err.max(), ref.flat[err.argmax()], (err / bound).max())
+    return float((err / bound).max())
+
+
+def run_layer_parity(w, rows=None, check_grads=True):
+    s, p = w.layers[0], w.params[0]
+    inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    # interval index: bit-exact
+    idx = binding.kan_interval_index(s, x).cpu().numpy()
+    np.testing.assert_array_equal(idx, oracle.interval_index(w.x, s.grid_lo, inv_h))
+    y = binding.kan_forward(s, x, coef, w_s, w_b)
+    g = binding.kan_backward(s, x, coef, w_s, w_b, gy) if check_grads else None
+    torch.cuda.synchronize()
+    sel = slice(None) if rows is None else rows
+    y_ref = oracle.kan_forward(w.x[sel], p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h, s.base_act)
+    assert_close(y[sel], y_ref, FWD_TOL, "y")
+    if check_grads:
+        if rows is None:
+            ref = oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h,
+                                      s.base_act)
+            for name in ("gx", "gcoef", "gw_s", "gw_b"):
+                assert_close(g[name], ref[name], GRAD_TOL, name)
+        else:
+            ref = oracle.kan_backward(w.x[sel], p["coef"], p["w_s"], p["w_b"], w.gy[sel], s.G, s.k, s.grid_lo,
+                                      inv_h, s.base_act, want=("gx",))
+            assert_close(g["gx"][sel], ref["gx"], GRAD_TOL, "gx")
+    return y, g
+
+
+SWEEP = [
+    # B, n_in, n_out, G, k, outside
+    (1, 1, 1, 1, 1, 0.0),
+    (7, 2, 5, 5, 3, 0.3),
+    (1024, 5, 1, 5, 3, 0.1),
+    (333, 3, 64, 4, 2, 0.2),
+    (257, 17, 130, 9, 3, 0.25),        # ragged in every dimension, n_out even -> 2 outputs per lane
+    (130, 70, 260, 10, 3, 0.1),        # 4 outputs per lane with a ragged last tile
+    (96, 33, 512, 20, 3, 0.05),
+    (200, 8, 256, 64, 1, 0.2),
+    (65, 4, 7, 200, 3, 0.2),           # large grid, odd n_out
+]
+
+
+@pytest.mark.parametrize("B,n_in,n_out,G,k,outside", SWEEP)
+def test_layer_parity_sweep(B, n_in, n_out, G, k, outside):
+    w = workloads.random_kan_layer(100 + B + n_in + n_out, B, n_in, n_out, G, k, outside_frac=outside)
+    run_layer_parity(w)
+
+
+def test_no_base_term():
+    w = workloads.random_kan_layer(5, 100, 6, 64, 8, 3, base_act=0, outside_frac=0.3)
+    s, p = w.layers[0], w.params[0]
+    x, coef, w_s, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], w.gy))
+    inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+    y = binding.kan_forward(s, x, coef, w_s, None)
+    g = binding.kan_backward(s, x, coef, w_s, None, gy, want=("gx", "gcoef", "gw_s"))
+    y_ref = oracle.kan_forward(w.x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h, base_act=0)
+    ref = oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h, base_act=0)
+    assert_close(y, y_ref, FWD_TOL, "y")
+    for name in ("gx", "gcoef", "gw_s"):
+        assert_close(g[name], ref[name], GRAD_TOL, name)
+
+
+def test_degenerate_inputs():
+    """All samples far outside the grid (base only), exactly on knots, and non-finite x."""
+    s = workloads.KanLayerSpec(3, 64, 5, 3, -1.0, 1.0)
+    rng = np.random.default_rng(3)
+    p = workloads.kan_params(rng, s, 0.1, w_s_std=1.0, w_b_std=1.0)
+    inv_h = oracle.inv_h_of(-1.0, 1.0, 5)
+    knots = np.float32(-1.0 + 0.4 * (np.arange(-4, 11)))
+    x = np.float32(np.stack([np.full(15, 50.0), knots, -knots], axis=1))
+    gy = np.float32(rng.standard_normal((15, 64)))
+    xd, coef, w_s, w_b, gyd = (dev(a) for a in (x, p["coef"], p["w_s"], p["w_b"], gy))
+    y = binding.kan_forward(s, xd, coef, w_s, w_b)
+    g = binding.kan_backward(s, xd, coef, w_s, w_b, gyd)
+    assert_close(y, oracle.kan_forward(x, p["coef"], p["w_s"], p["w_b"], 5, 3, -1.0, inv_h), FWD_TOL, "y")
+    ref = oracle.kan_backward(x, p["coef"], p["w_s"], p["w_b"], gy, 5, 3, -1.0, inv_h)
+    for name in ref:
+        assert_close(g[name], ref[name], GRAD_TOL, name)
+    # the first input never touches the spline: its coefficient gradient is exactly zero
+    assert (g["gcoef"][0] == 0).all() and (g["gw_s"][0] == 0).all()
+    np.testing.assert_array_equal(binding.kan_interval_index(s, xd).cpu().numpy(),
+                                  oracle.interval_index(x, -1.0, inv_h))
+    # non-finite x: spline term dropped, index saturates like the definition
+    bad = np.float32([[np.inf, -np.inf, np.nan]])
+    np.testing.assert_array_equal(binding.kan_interval_index(s, dev(bad)).cpu().numpy(),
+                                  oracle.interval_index(bad, -1.0, inv_h))
+
+
+def test_empty_batch_and_argument_errors():
+    s = workloads.KanLayerSpec(4, 8, 5, 3, -1.0, 1.0)
+    rng = np.random.default_rng(1)
+    p = {n: dev(a) for n, a in workloads.kan_params(rng, s, 0.1, w_s_std=1.0, w_b_std=1.0).items()}
+    x0 = torch.empty((0, 4), device="cuda")
+    y = binding.kan_forward(s, x0, p["coef"], p["w_s"], p["w_b"])
+    assert y.shape == (0, 8)
+    x = torch.zeros((3, 4), device="cuda")
+    lib = binding.load()
+    import ctypes
+    d = binding.kan_desc(s)
+    ws = torch.empty(binding.kan_workspace_bytes(s, 3), dtype=torch.uint8, device="cuda")
+    yv = torch.empty((3, 8), device="cuda")
+    ok = lambda: lib.kan_forward(ctypes.byref(d), 3, x.data_ptr(), p["coef"].data_ptr(), p["w_s"].data_ptr(),
+                                 p["w_b"].data_ptr(), yv.data_ptr(), ws.data_ptr(), ws.numel(), None)
+    assert ok() == binding.KAN_OK
+    assert lib.kan_forward(ctypes.byref(d), 3, None, p["coef"].data_ptr(), p["w_s"].data_ptr(), p["w_b"].data_ptr(),
+                           yv.data_ptr(), ws.data_ptr(), ws.numel(), None) == binding.KAN_ERR_INVALID_ARG
+    assert lib.kan_forward(ctypes.byref(d), 3, x.data_ptr(), p["coef"].data_ptr(), p["w_s"].data_ptr(),
+                           p["w_b"].data_ptr(), yv.data_ptr(), ws.data_ptr(), 16, None) == binding.KAN_ERR_WORKSPACE
+    assert lib.kan_forward(ctypes.byref(d), 3, x.data_ptr(), p["coef"].data_ptr(), p["w_s"].data_ptr(),
+                           p["w_b"].data_ptr(), yv.data_ptr(), None, 0, None) == binding.KAN_ERR_WORKSPACE
+    for bad in (dict(k=0), dict(k=4), dict(base_act=7)):
+        d2 = binding.kan_desc(s)
+        for n, v in bad.items():
+            setattr(d2, n, v)
+        assert lib.kan_workspace_bytes(ctypes.byref(d2), 3, 0) == 0
+        assert lib.kan_forward(ctypes.byref(d2), 3, x.data_ptr(), p["coef"].data_ptr(), p["w_s"].data_ptr(),
+                               p["w_b"].data_ptr(), yv.data_ptr(), ws.data_ptr(), ws.numel(),
+                               None) == binding.KAN_ERR_UNSUPPORTED
+    d3 = binding.kan_desc(s)
+    d3.grid_hi = -1.0
+    assert lib.kan_forward(ctypes.byref(d3), 3, x.data_ptr(), p["coef"].data_ptr(), p["w_s"].data_ptr(),
+                           p["w_b"].data_ptr(), yv.data_ptr(), ws.data_ptr(), ws.numel(),
+                           None) == binding.KAN_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
+def test_backward_is_bit_reproducible_and_partial_outputs():
+    w = workloads.random_kan_layer(77, 3000, 24, 128, 12, 3, outside_frac=0.1)
+    s, p = w.layers[0], w.params[0]
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    a = binding.kan_backward(s, x, coef, w_s, w_b, gy)
+    b = binding.kan_backward(s, x, coef, w_s, w_b, gy)
+    for name in a:
+        assert torch.equal(a[name], b[name]), name
+    only = binding.kan_backward(s, x, coef, w_s, w_b, gy, want=("gcoef",))
+    assert set(only) == {"gcoef"} and torch.equal(only["gcoef"], a["gcoef"])
+    only = binding.kan_backward(s, x, coef, w_s, w_b, gy, want=("gx", "gw_b"))
+    assert torch.equal(only["gx"], a["gx"]) and torch.equal(only["gw_b"], a["gw_b"])
+
+
+def test_config1_two_layer_chain_with_mse():
+    """Tiny KAN [2,5,1], batch 1024, MSE against sin(pi x0) + x1^2: forward and the chained backward."""
+    w = workloads.config1()
+    S, P = w.layers, w.params
+    ih = [oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G) for s in S]
+    Pd = [{n: dev(a) for n, a in p.items()} for p in P]
+    x = dev(w.x)
+    h1 = binding.kan_forward(S[0], x, Pd[0]["coef"], Pd[0]["w_s"], Pd[0]["w_b"])
+    y = binding.kan_forward(S[1], h1, Pd[1]["coef"], Pd[1]["w_s"], Pd[1]["w_b"])
+    gy = (2.0 / w.B) * (y - dev(w.target))          # host-side loss glue, not part of the layer
+    g2 = binding.kan_backward(S[1], h1, Pd[1]["coef"], Pd[1]["w_s"], Pd[1]["w_b"], gy)
+    g1 = binding.kan_backward(S[0], x, Pd[0]["coef"], Pd[0]["w_s"], Pd[0]["w_b"], g2["gx"])
+    # oracle chain in fp64, fed the fp32 activations the device produced at each layer boundary
+    h1n = h1.cpu().numpy()
+    h1_ref = oracle.kan_forward(w.x, P[0]["coef"], P[0]["w_s"], P[0]["w_b"], 5, 3, -1.0, ih[0])
+    assert_close(h1, h1_ref, FWD_TOL, "h1")
+    y_ref = oracle.kan_forward(h1n, P[1]["coef"], P[1]["w_s"], P[1]["w_b"], 5, 3, -1.0, ih[1])
+    assert_close(y, y_ref, FWD_TOL, "y")
+    gyn = gy.cpu().numpy()
+    r2 = oracle.kan_backward(h1n, P[1]["coef"], P[1]["w_s"], P[1]["w_b"], gyn, 5, 3, -1.0, ih[1])
+    for name in r2:
+        assert_close(g2[name], r2[name], GRAD_TOL, "layer2 " + name)
+    r1 = oracle.kan_backward(w.x, P[0]["coef"], P[0]["w_s"], P[0]["w_b"], g2["gx"].cpu().numpy(), 5, 3, -1.0, ih[0])
+    for name in r1:
+        assert_close(g1[name], r1[name], GRAD_TOL, "layer1 " + name)
+
+
+def test_config2_full_size():
+    """64->64, G=10, batch 65536 with 5% of the samples outside the grid: every output element."""
+    run_layer_parity(workloads.config2())
+
+
+def test_config3_full_size_sampled():
+    """512->512, G=20, batch 16384 in the launch configuration the benchmark times.  The oracle checks a
+    sample of rows for y and gx, and all of gcoef / gw_s / gw_b for a sample of inputs (each input's
+    parameter gradients depend on the whole batch but on no other input)."""
+    w = workloads.config3()
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(w.B, 192, replace=False))
+    y, g = run_layer_parity(w, rows=rows)
+    s, p = w.layers[0], w.params[0]
+    inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+    ins = np.sort(rng.choice(s.n_in, 6, replace=False))
+    ref = oracle.kan_backward(w.x[:, ins], p["coef"][ins], p["w_s"][ins], p["w_b"][ins], w.gy, s.G, s.k,
+                              s.grid_lo, inv_h, want=("gcoef", "gw_s", "gw_b"))
+    for name in ("gcoef", "gw_s", "gw_b"):
+        assert_close(g[name][torch.from_numpy(ins).cuda()], ref[name], GRAD_TOL, name)
+    # property that holds at any size: inside the grid the window weights sum to one, so
+    # sum_m gcoef[i][m][j] / w_s[i][j] == sum_b gy[b][j] for every input i
+    col = torch.from_numpy(w.gy.astype(np.float64).sum(0)).cuda()
+    lhs = (g["gcoef"].double() / dev(p["w_s"]).double()[:, None, :]).sum(1)
+    assert float((lhs - col[None, :]).abs().max()) < 2e-2 * float(col.abs().max() + 1)
+
+
+def test_config4_large_grid_sampled():
+    w = workloads.config4()
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(w.B, 256, replace=False))
+    y, g = run_layer_parity(w, rows=rows)
+    s, p = w.layers[0], w.params[0]
+    inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+    ins = np.sort(rng.choice(s.n_in, 6, replace=False))
+    ref = oracle.kan_backward(w.x[:, ins], p["coef"][ins], p["w_s"][ins], p["w_b"][ins], w.gy, s.G, s.k,
+                              s.grid_lo, inv_h, want=("gcoef", "gw_s", "gw_b"))
+    for name in ("gcoef", "gw_s", "gw_b"):
+        assert_close(g[name][torch.from_numpy(ins).cuda()], ref[name], GRAD_TOL, name)

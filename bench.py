@@ -1,0 +1,127 @@
+#!/usr/bin/env python3
+"""Benchmark of the KAN layer hot path on one MI355X.
+
+One step = kan_forward + kan_backward (all four gradients) of the 512->512, G=20, k=3 layer on a
+batch of 16384 synthetic samples resident in HBM.  Prints one JSON line with the whole-job
+throughput in edge-evaluations/s, the roofline position of the dominant kernel (its duration is
+measured with HIP events on the launch stream, inside the timed region) and the CPU oracle timed on
+the host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# algorithmic flops per edge evaluation of each kernel family (K = k+1 window multiply-adds for the
+# spline plus one multiply-add for the base term, 2 flops each)
+def flops_per_edge(k):
+    return 2 * (k + 1) + 2
+
+
+KERNEL_ROLE = {  # kernel family -> which third of the fwd+bwd work it carries
+    "forward_generic": "forward", "dx_generic": "dx", "dparam_generic": "dparam",
+    "forward_lds": "forward", "dx_lds": "dx", "dparam_sorted": "dparam",
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2408_11200_amd import binding, roofline, workloads
+
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        return 2
+    binding.load()
+
+    w = {"c2": workloads.config2, "c3": workloads.config3, "c4": workloads.config4}[args.workload]()
+    s, p = w.layers[0], w.params[0]
+    dev = lambda a: torch.from_numpy(a).cuda()
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    B = w.B
+    y = torch.empty((B, s.n_out), device="cuda")
+    out = {"gx": torch.empty((B, s.n_in), device="cuda"), "gcoef": torch.empty_like(coef),
+           "gw_s": torch.empty_like(w_s), "gw_b": torch.empty_like(w_b)}
+    ws_f = torch.empty(binding.kan_workspace_bytes(s, B, binding.PASS_FORWARD), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.kan_workspace_bytes(s, B, binding.PASS_BACKWARD), dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.kan_forward(s, x, coef, w_s, w_b, y=y, ws=ws_f)
+        binding.kan_backward(s, x, coef, w_s, w_b, gy, out=out, ws=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.kan_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    binding.kan_profile_enable(False)
+    kt = binding.kan_profile_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    edges = roofline.edge_evals(B, s.n_in, s.n_out)
+    value = edges / (ms_per_step * 1e-3)
+
+    # dominant kernel = largest average duration
+    avg = {n: tot / max(cnt, 1) for n, (tot, cnt) in kt.items()}
+    dom = max(avg, key=avg.get)
+    dom_ms = avg[dom]
+    if dom in KERNEL_ROLE:
+        flops = flops_per_edge(s.k) * edges
+        achieved = flops / (dom_ms * 1e-3) / 1e12
+    else:
+        flops, achieved = None, None
+    peak = roofline.MI355X_FP32_VECTOR_FLOPS / 1e12
+    rl = {"bound": "alu", "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+          "frac": (achieved / peak) if achieved else None, "traffic": None,
+          "kernel_ms": dom_ms,
+          "peak_unpacked": roofline.MI355X_FP32_VECTOR_FLOPS_UNPACKED / 1e12,
+          "frac_unpacked": (achieved / (roofline.MI355X_FP32_VECTOR_FLOPS_UNPACKED / 1e12)) if achieved else None,
+          "whole_path_frac": roofline.algorithmic_flops_per_edge(s.k + 1) * value / roofline.MI355X_FP32_VECTOR_FLOPS,
+          "kernels_ms": {n: round(v, 4) for n, v in sorted(avg.items())}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+        reps = 3
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            oracle.kan_forward(w.x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h, s.base_act)
+            oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h, s.base_act)
+        c1 = time.perf_counter()
+        cpu = {"value": reps * edges / (c1 - c0), "unit": "edge-evals/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "the whole batch (%d rows), forward + backward, %d repetitions, %.1f s" % (B, reps, c1 - c0)}
+
+    line = {"metric": "KAN layer fwd+bwd edge-evals/sec (B*n_in*n_out)", "value": value, "unit": "edge-evals/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+            "data": "synthetic",
+            "config": {"workload": w.name, "B": B, "n_in": s.n_in, "n_out": s.n_out, "G": s.G, "k": s.k,
+                       "grid": [s.grid_lo, s.grid_hi], "pass": "forward+backward"},
+            "roofline": rl, "cpu_baseline": cpu}
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -118,6 +118,23 @@ int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const fl
 int kan_interval_index(const kan_layer_desc *desc, int64_t n, const float *x, int32_t *idx,
                        void *stream);
 
+/* ---- diagnostics ------------------------------------------------------------------------ */
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
+   bracketed by a pair of HIP events on the launch stream (the only library state that outlives
+   a call; at most 8192 launches are recorded, later ones run untimed).  kan_profile_enable(1)
+   clears earlier records, kan_profile_enable(0) stops recording.  kan_profile_read waits for
+   the recorded events, fills up to `capacity` entries (one per kernel family, `name` is a
+   static string) and returns the number of families seen, or a negative kan_status.
+   Not thread-safe; meant for one benchmarking thread. */
+typedef struct kan_kernel_time {
+    const char *name;
+    double total_ms;
+    int64_t launches;
+} kan_kernel_time;
+int kan_profile_enable(int on);
+int kan_profile_read(kan_kernel_time *out, int capacity);
+
 /* ---- UKAN ------------------------------------------------------------------------------ */
 
 /* Scratch bytes for ukan_cg_forward / ukan_cg_backward.  max_groups bounds, per input, the

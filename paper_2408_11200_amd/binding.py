@@ -21,6 +21,7 @@ KAN_ERR_HIP = -5
 PASS_FORWARD, PASS_BACKWARD = 0, 1
 
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
+           "kan_profile_enable", "kan_profile_read",
            "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_group_index"]
 
 
@@ -42,6 +43,10 @@ class UkanParams(ctypes.Structure):
 
 class UkanGrads(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("gE", "gW1", "gb1", "gW2", "gb2", "gscale", "gw_b")]
+
+
+class KanKernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("total_ms", ctypes.c_double), ("launches", ctypes.c_int64)]
 
 
 class KanError(RuntimeError):
@@ -72,6 +77,10 @@ def load():
     lib.kan_backward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kan_interval_index.restype = ctypes.c_int
     lib.kan_interval_index.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp]
+    lib.kan_profile_enable.restype = ctypes.c_int
+    lib.kan_profile_enable.argtypes = [ctypes.c_int]
+    lib.kan_profile_read.restype = ctypes.c_int
+    lib.kan_profile_read.argtypes = [ctypes.POINTER(KanKernelTime), ctypes.c_int]
     lib.ukan_workspace_bytes.restype = sz
     lib.ukan_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i32, ctypes.c_int]
     lib.ukan_cg_forward.restype = ctypes.c_int
@@ -171,6 +180,19 @@ def kan_interval_index(spec, x, stream=None):
     if rc != KAN_OK:
         raise KanError(rc, "kan_interval_index")
     return idx
+
+
+def kan_profile_enable(on):
+    load().kan_profile_enable(1 if on else 0)
+
+
+def kan_profile_read():
+    """{kernel family: (total_ms, launches)} of the launches recorded since kan_profile_enable(True)."""
+    arr = (KanKernelTime * 64)()
+    n = load().kan_profile_read(arr, 64)
+    if n < 0:
+        raise KanError(n, "kan_profile_read")
+    return {arr[q].name.decode(): (arr[q].total_ms, int(arr[q].launches)) for q in range(min(n, 64))}
 
 
 # ------------------------------------------------------------------ UKAN ----

@@ -367,6 +367,7 @@ hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float 
 {
     if (n == 0) return hipSuccess;
     unsigned blocks = (unsigned)((n + 255) / 256);
+    prof::Timed tm("interval_index", st);
     interval_index_kernel<<<blocks, 256, 0, st>>>(x, idx, n, lo, inv_h);
     return hipGetLastError();
 }
@@ -377,6 +378,7 @@ hipError_t launch_fold_scale(const float *coef, const float *w_s, float *cf, int
     int64_t total = (int64_t)n_in * rows * n_out;
     int64_t want = (total + 255) / 256;
     unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+    prof::Timed tm("fold_scale", st);
     fold_scale_kernel<<<blocks, 256, 0, st>>>(coef, w_s, cf, n_in, rows, n_out);
     return hipGetLastError();
 }
@@ -387,6 +389,7 @@ static hipError_t forward_r(const SplineGeom &g, const float *x, const float *cf
 {
     constexpr int T = (R == 4) ? 8 : 16;
     dim3 grid((unsigned)((B + 4 * T - 1) / (4 * T)), (unsigned)((g.n_out + 64 * R - 1) / (64 * R)));
+    prof::Timed tm("forward_generic", st);
     forward_generic_kernel<R, T><<<grid, 256, 0, st>>>(g, x, cf, w_b, y, B);
     return hipGetLastError();
 }
@@ -407,6 +410,7 @@ static hipError_t dx_r(const SplineGeom &g, const float *x, const float *cf, con
 {
     constexpr int T = 8;
     dim3 grid((unsigned)((B + 4 * T - 1) / (4 * T)));
+    prof::Timed tm("dx_generic", st);
     dx_generic_kernel<R, T><<<grid, 256, 0, st>>>(g, x, cf, w_b, gy, gx, B);
     return hipGetLastError();
 }
@@ -434,6 +438,7 @@ hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const floa
     size_t lds = dparam_lds(g.rows, R);
     dim3 grid((unsigned)g.n_in, (unsigned)((g.n_out + 64 * R - 1) / (64 * R)), (unsigned)n_chunks);
     hipError_t e = hipSuccess;
+    prof::Timed tm("dparam_generic", st);
     switch (R) {
     case 4:
         dparam_generic_kernel<4><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
@@ -458,6 +463,7 @@ hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const 
                                 int n_chunks, hipStream_t st)
 {
     int64_t total = (int64_t)n_in * n_out;
+    prof::Timed tm("dparam_reduce", st);
     dparam_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part_c, part_b, coef, w_s, gcoef, gw_s,
                                                                         gw_b, n_in, rows, n_out, n_chunks);
     return hipGetLastError();

@@ -8,6 +8,20 @@
 
 namespace kan {
 
+// Optional per-launch timing (see kan_profile_enable in kan.h).  A Timed object brackets one
+// kernel launch with two events when profiling is on and does nothing otherwise.
+namespace prof {
+bool enabled();
+void begin(const char *family, hipStream_t st);
+void end(hipStream_t st);
+struct Timed {
+    hipStream_t st;
+    bool on;
+    Timed(const char *family, hipStream_t s) : st(s), on(enabled()) { if (on) begin(family, st); }
+    ~Timed() { if (on) end(st); }
+};
+}  // namespace prof
+
 hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float lo, float inv_h,
                                  hipStream_t st);
 hipError_t launch_fold_scale(const float *coef, const float *w_s, float *cf, int n_in, int rows, int n_out,

@@ -73,6 +73,11 @@ def inv_h_of(grid_lo, grid_hi, G):
     return np.float32(G) / (np.float32(grid_hi) - np.float32(grid_lo))
 
 
+def inv_h_of_spacing(h):
+    """UKAN: the fp32 reciprocal of the fp32 grid spacing, 1.0f / h."""
+    return np.float32(1.0) / np.float32(h)
+
+
 def silu(x):
     lib = _load()
     return np.vectorize(lambda v: lib.okan_silu(float(v)))(np.asarray(x, dtype=np.float64))

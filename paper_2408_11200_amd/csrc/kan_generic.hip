@@ -89,16 +89,25 @@ __global__ __launch_bounds__(256) void forward_generic_kernel(SplineGeom g, cons
     const bool j_ok = j < g.n_out;      // n_out is a multiple of R
     const int jc = j_ok ? j : 0;
 
-    float acc[T][R];
+    // two-level sum over the inputs: `acc` collects kFoldInputs inputs, then is folded into
+    // `tot`; keeps the rounding error of a long fp32 sum well inside the tolerance
+    constexpr int kFoldInputs = 32;
+    float acc[T][R], tot[T][R];
 #pragma unroll
     for (int t = 0; t < T; ++t)
 #pragma unroll
-        for (int r = 0; r < R; ++r) acc[t][r] = 0.0f;
+        for (int r = 0; r < R; ++r) { acc[t][r] = 0.0f; tot[t][r] = 0.0f; }
 
     const int my_t = lane % T, my_ii = lane / T;
     const int64_t my_b = (b0 + my_t < B) ? b0 + my_t : B - 1;
 
     for (int i0 = 0; i0 < g.n_in; i0 += IPV) {
+        if (i0 % kFoldInputs == 0 && i0 > 0) {
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < R; ++r) { tot[t][r] += acc[t][r]; acc[t][r] = 0.0f; }
+        }
         const int my_i = i0 + my_ii;
         const bool i_ok = my_i < g.n_in;
         const int ic = i_ok ? my_i : g.n_in - 1;
@@ -138,8 +147,11 @@ __global__ __launch_bounds__(256) void forward_generic_kernel(SplineGeom g, cons
     }
     if (j_ok) {
 #pragma unroll
-        for (int t = 0; t < T; ++t)
-            if (b0 + t < B) store_vec<R>(y + (b0 + t) * g.n_out + j, acc[t]);
+        for (int t = 0; t < T; ++t) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) tot[t][r] += acc[t][r];
+            if (b0 + t < B) store_vec<R>(y + (b0 + t) * g.n_out + j, tot[t]);
+        }
     }
 }
 

@@ -1,6 +1,257 @@
-// placeholder until the UKAN path lands
+// C ABI of the UKAN layer: workspace layout, the single read-back of the group span, and
+// the sequence of kernels (range -> CG forward -> spline kernels -> CG backward).
+// See include/kan.h for the contract.
 #include "kan.h"
-extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *, int64_t, int32_t, int) { return 0; }
-extern "C" int ukan_cg_forward(const ukan_layer_desc *, int64_t, const float *, const ukan_params *, float *, int32_t, void *, size_t, void *) { return KAN_ERR_UNSUPPORTED; }
-extern "C" int ukan_cg_backward(const ukan_layer_desc *, int64_t, const float *, const ukan_params *, const float *, float *, const ukan_grads *, int32_t, void *, size_t, void *) { return KAN_ERR_UNSUPPORTED; }
-extern "C" int ukan_group_index(const ukan_layer_desc *, int64_t, const float *, int32_t *, int32_t *, int32_t *, void *) { return KAN_ERR_UNSUPPORTED; }
+#include "kan_launch.hpp"
+#include "ukan_launch.hpp"
+
+using namespace kan;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int check_desc(const ukan_layer_desc *d)
+{
+    if (!d) return KAN_ERR_INVALID_ARG;
+    if (d->n_in <= 0 || d->n_out <= 0 || !(d->h > 0.0f)) return KAN_ERR_INVALID_ARG;
+    if (d->d_pe <= 0 || d->d_feat < 0 || d->d_hidden <= 0) return KAN_ERR_INVALID_ARG;
+    if (d->k < 1 || d->k > 3) return KAN_ERR_UNSUPPORTED;
+    if (d->d_pe % 2 != 0) return KAN_ERR_UNSUPPORTED;         // sin/cos pairs
+    if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
+    return KAN_OK;
+}
+
+// Offsets (bytes) of every scratch region for `n_g` generator rows per input.
+struct Layout {
+    size_t cmin, cmax, g_first, n_groups, cell_base, summary;
+    size_t hid, cf;                                   // forward
+    size_t z, pre, raw, part_c, part_b, gout, gpre, split;   // backward only
+    size_t total;
+};
+
+int split_slices(int64_t rows) { int64_t s = (rows + 511) / 512; return (int)(s < 1 ? 1 : (s > 64 ? 64 : s)); }
+
+Layout make_layout(const ukan_layer_desc *d, int64_t n_g, int n_chunks, int pass)
+{
+    const size_t K = (size_t)d->k + 1, n_in = (size_t)d->n_in, n_out = (size_t)d->n_out;
+    const size_t rows = n_in * (size_t)n_g, n_o = K * n_out, dz = (size_t)d->d_feat + d->d_pe, dh = (size_t)d->d_hidden;
+    const size_t table = align_up(rows * n_o * sizeof(float));
+    Layout L;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t here = at; at += align_up(bytes); return here; };
+    L.cmin = take(n_in * 4); L.cmax = take(n_in * 4); L.g_first = take(n_in * 4);
+    L.n_groups = take(n_in * 4); L.cell_base = take(n_in * 4); L.summary = take(256);
+    L.hid = take(rows * dh * 4);
+    L.cf = take(table);
+    L.z = L.pre = L.raw = L.part_c = L.part_b = L.gout = L.gpre = L.split = 0;
+    if (pass == KAN_PASS_BACKWARD) {
+        L.z = take(rows * dz * 4);
+        L.pre = take(rows * dh * 4);
+        L.raw = take(table);
+        L.part_c = take((size_t)n_chunks * table);
+        L.part_b = take((size_t)n_chunks * n_in * n_out * 4);
+        L.gout = take(table);
+        L.gpre = take(rows * dh * 4);
+        size_t s1 = (size_t)split_slices((int64_t)rows) * dh * n_o * 4;      // gW2 partials
+        size_t s2 = (size_t)split_slices((int64_t)rows) * dz * dh * 4;       // gW1 partials
+        size_t s3 = (size_t)colsum_slices((int64_t)rows) * (n_o > dh ? n_o : dh) * 4;
+        size_t s = s1 > s2 ? s1 : s2;
+        L.split = take(s > s3 ? s : s3);
+    }
+    L.total = at;
+    return L;
+}
+
+ChunkPlan chunks_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
+{
+    return plan_chunks(B, d->n_in, max_groups * (d->k + 1), d->n_out);
+}
+
+struct Prepared {
+    SplineGeom g;
+    Layout L;
+    int n_g;
+    ChunkPlan cp;
+};
+
+// steps 1-2 of the pass: group range, read-back, CG forward into the table(s)
+int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_params *p, int32_t max_groups,
+            char *ws, int pass, hipStream_t st, Prepared *out)
+{
+    const int K = d->k + 1;
+    const float inv_h = 1.0f / d->h;
+    out->cp = chunks_for(d, B, max_groups);
+    Layout L0 = make_layout(d, max_groups, out->cp.n_chunks, pass);     // meta offsets do not depend on n_g
+    int32_t *cmin = (int32_t *)(ws + L0.cmin), *cmax = (int32_t *)(ws + L0.cmax);
+    int32_t *g_first = (int32_t *)(ws + L0.g_first), *n_groups = (int32_t *)(ws + L0.n_groups);
+    int32_t *cell_base = (int32_t *)(ws + L0.cell_base), *summary = (int32_t *)(ws + L0.summary);
+    if (launch_range(x, B, d->n_in, inv_h, K, cmin, cmax, g_first, n_groups, cell_base, summary, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    int32_t span = 0;
+    if (hipMemcpyAsync(&span, summary, sizeof(span), hipMemcpyDeviceToHost, st) != hipSuccess) return KAN_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return KAN_ERR_HIP;
+    if (span < 2 || span > max_groups) return KAN_ERR_RANGE;
+    out->n_g = span;
+    out->L = make_layout(d, span, out->cp.n_chunks, pass);
+    const Layout &L = out->L;
+    const int64_t rows = (int64_t)d->n_in * span;
+    const int64_t n_o = (int64_t)K * d->n_out;
+
+    const bool bwd = pass == KAN_PASS_BACKWARD;
+    float *hid = (float *)(ws + L.hid);
+    if (launch_cg_hidden(p->E, p->W1, p->b1, g_first, bwd ? (float *)(ws + L.z) : nullptr,
+                         bwd ? (float *)(ws + L.pre) : nullptr, hid, d->n_in, span, d->d_pe, d->d_feat,
+                         d->d_hidden, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    GemmArgs a = {};
+    a.A = hid; a.a_rs = d->d_hidden; a.a_cs = 1;
+    a.B = p->W2; a.b_rs = n_o; a.b_cs = 1;
+    a.C = (float *)(ws + L.cf); a.ldc = n_o;
+    a.M = rows; a.N = n_o; a.K = d->d_hidden;
+    a.k_slice = d->d_hidden; a.c_slice = 0;
+    a.bias = p->b2; a.scale = p->scale; a.C2 = bwd ? (float *)(ws + L.raw) : nullptr;
+    a.rows_per_input = span; a.n_out = d->n_out;
+    if (launch_gemm(a, EPI_CG_OUT, 1, "cg_output_gemm", st) != hipSuccess) return KAN_ERR_HIP;
+
+    SplineGeom &g = out->g;
+    g.n_in = d->n_in; g.n_out = d->n_out;
+    g.rows = span * K; g.k = d->k;
+    g.lo = 0.0f; g.inv_h = inv_h;
+    g.cell_base = cell_base;
+    g.base_act = d->base_act;
+    return KAN_OK;
+}
+
+int check_common(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_params *p, int32_t max_groups,
+                 void *ws, size_t ws_bytes, int pass)
+{
+    int rc = check_desc(d);
+    if (rc != KAN_OK) return rc;
+    if (B < 0 || max_groups < 2) return KAN_ERR_INVALID_ARG;
+    if (B == 0) return KAN_OK;
+    if (!x || !p || !p->E || !p->W1 || !p->b1 || !p->W2 || !p->b2 || !p->scale) return KAN_ERR_INVALID_ARG;
+    if (d->base_act != KAN_BASE_NONE && !p->w_b) return KAN_ERR_INVALID_ARG;
+    size_t need = ukan_workspace_bytes(d, B, max_groups, pass);
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || need == 0 || ws_bytes < need) return KAN_ERR_WORKSPACE;
+    return KAN_OK;
+}
+
+}  // namespace
+
+extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *desc, int64_t B, int32_t max_groups, int pass)
+{
+    if (check_desc(desc) != KAN_OK || B < 0 || max_groups < 2) return 0;
+    if (pass != KAN_PASS_FORWARD && pass != KAN_PASS_BACKWARD) return 0;
+    ChunkPlan cp = chunks_for(desc, B, max_groups);
+    return make_layout(desc, max_groups, cp.n_chunks, pass).total;
+}
+
+extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                               float *y, int32_t max_groups, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_FORWARD);
+    if (rc != KAN_OK || B == 0) return rc;
+    if (!y) return KAN_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    Prepared pr;
+    rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr);
+    if (rc != KAN_OK) return rc;
+    if (launch_forward_generic(pr.g, x, (const float *)((char *)ws + pr.L.cf), p->w_b, y, B, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    return KAN_OK;
+}
+
+extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                                const float *gy, float *gx, const ukan_grads *g, int32_t max_groups, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_BACKWARD);
+    if (rc != KAN_OK || B == 0) return rc;
+    if (!gy) return KAN_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    char *w = (char *)ws;
+    Prepared pr;
+    rc = prepare(desc, B, x, p, max_groups, w, KAN_PASS_BACKWARD, st, &pr);
+    if (rc != KAN_OK) return rc;
+    const Layout &L = pr.L;
+    const int K = desc->k + 1, dh = desc->d_hidden, dz = desc->d_feat + desc->d_pe;
+    const int64_t rows = (int64_t)desc->n_in * pr.n_g, n_o = (int64_t)K * desc->n_out;
+
+    if (gx && launch_dx_generic(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st) != hipSuccess)
+        return KAN_ERR_HIP;
+
+    const bool cg_grads = g && (g->gE || g->gW1 || g->gb1 || g->gW2 || g->gb2);
+    const bool want_b = g && g->gw_b && desc->base_act != KAN_BASE_NONE;
+    if (!(cg_grads || (g && (g->gscale || g->gw_b)))) return KAN_OK;
+    if (!dparam_generic_supported(pr.g.rows)) return KAN_ERR_UNSUPPORTED;
+
+    // table gradient: partial sums per batch chunk, then  gout = scale * sum,  gscale = sum_m raw * sum
+    float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
+    float *gout = (float *)(w + L.gout);
+    if (launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks, pr.cp.chunk_len,
+                              st) != hipSuccess)
+        return KAN_ERR_HIP;
+    if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
+                             cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,
+                             pr.cp.n_chunks, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    if (!cg_grads) return KAN_OK;
+
+    float *split = (float *)(w + L.split);
+    const float *hid = (const float *)(w + L.hid);
+    float *gpre = (float *)(w + L.gpre);
+    const int slices = split_slices(rows);
+    int64_t k_slice = (rows + slices - 1) / slices;
+    k_slice = (k_slice + 15) / 16 * 16;
+
+    if (g->gb2 && launch_colsum(gout, split, g->gb2, rows, (int)n_o, st) != hipSuccess) return KAN_ERR_HIP;
+    if (g->gW2) {       // gW2[c][o] = sum_rows hid[row][c] * gout[row][o]
+        GemmArgs a = {};
+        a.A = hid; a.a_rs = 1; a.a_cs = dh;
+        a.B = gout; a.b_rs = n_o; a.b_cs = 1;
+        a.C = split; a.ldc = n_o; a.M = dh; a.N = n_o; a.K = rows;
+        a.k_slice = k_slice; a.c_slice = (int64_t)dh * n_o;
+        const int used = (int)((rows + k_slice - 1) / k_slice);
+        if (launch_gemm(a, EPI_PLAIN, used, "cg_gW2_gemm", st) != hipSuccess) return KAN_ERR_HIP;
+        if (launch_slice_sum(split, g->gW2, (int64_t)dh * n_o, used, st) != hipSuccess) return KAN_ERR_HIP;
+    }
+    if (g->gE || g->gW1 || g->gb1) {
+        GemmArgs a = {};    // gpre[row][c] = (sum_o gout[row][o] * W2[c][o]) * silu'(pre[row][c])
+        a.A = gout; a.a_rs = n_o; a.a_cs = 1;
+        a.B = p->W2; a.b_rs = 1; a.b_cs = n_o;
+        a.C = gpre; a.ldc = dh; a.M = rows; a.N = dh; a.K = n_o;
+        a.k_slice = n_o; a.c_slice = 0;
+        a.aux = (const float *)(w + L.pre);
+        if (launch_gemm(a, EPI_SILU_GRAD, 1, "cg_ghid_gemm", st) != hipSuccess) return KAN_ERR_HIP;
+        if (g->gb1 && launch_colsum(gpre, split, g->gb1, rows, dh, st) != hipSuccess) return KAN_ERR_HIP;
+        if (g->gW1) {   // gW1[p][c] = sum_rows z[row][p] * gpre[row][c]
+            GemmArgs b = {};
+            b.A = (const float *)(w + L.z); b.a_rs = 1; b.a_cs = dz;
+            b.B = gpre; b.b_rs = dh; b.b_cs = 1;
+            b.C = split; b.ldc = dh; b.M = dz; b.N = dh; b.K = rows;
+            b.k_slice = k_slice; b.c_slice = (int64_t)dz * dh;
+            const int used = (int)((rows + k_slice - 1) / k_slice);
+            if (launch_gemm(b, EPI_PLAIN, used, "cg_gW1_gemm", st) != hipSuccess) return KAN_ERR_HIP;
+            if (launch_slice_sum(split, g->gW1, (int64_t)dz * dh, used, st) != hipSuccess) return KAN_ERR_HIP;
+        }
+        if (g->gE && desc->d_feat > 0 &&
+            launch_embed_grad(p->W1, gpre, g->gE, desc->n_in, pr.n_g, desc->d_feat, dh, st) != hipSuccess)
+            return KAN_ERR_HIP;
+    }
+    return KAN_OK;
+}
+
+extern "C" int ukan_group_index(const ukan_layer_desc *desc, int64_t n, const float *x, int32_t *cell,
+                                int32_t *group, int32_t *offset, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != KAN_OK) return rc;
+    if (n < 0) return KAN_ERR_INVALID_ARG;
+    if (n == 0) return KAN_OK;
+    if (!x) return KAN_ERR_INVALID_ARG;
+    if (launch_group_index(x, cell, group, offset, n, 1.0f / desc->h, desc->k + 1, (hipStream_t)stream) != hipSuccess)
+        return KAN_ERR_HIP;
+    return KAN_OK;
+}

@@ -1,0 +1,68 @@
+"""The C-ABI library loads without a GPU and exports every function include/kan.h declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2408_11200_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return ctypes.CDLL(binding.LIB_PATH)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "kan.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith(("kan_", "ukan_"))})
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"kan_forward", "kan_backward", "ukan_cg_forward", "ukan_cg_backward"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_host_only_calls(lib):
+    """Calls that never touch the device: status strings and workspace sizes."""
+    lib.kan_strerror.restype = ctypes.c_char_p
+    assert lib.kan_strerror(0) == b"ok"
+    assert b"workspace" in lib.kan_strerror(binding.KAN_ERR_WORKSPACE)
+    lib.kan_workspace_bytes.restype = ctypes.c_size_t
+    lib.kan_workspace_bytes.argtypes = [ctypes.POINTER(binding.KanLayerDesc), ctypes.c_int64, ctypes.c_int]
+    d = binding.KanLayerDesc(512, 512, 20, 3, -1.0, 1.0, 1)
+    fwd = lib.kan_workspace_bytes(ctypes.byref(d), 16384, binding.PASS_FORWARD)
+    bwd = lib.kan_workspace_bytes(ctypes.byref(d), 16384, binding.PASS_BACKWARD)
+    assert fwd >= 512 * 23 * 512 * 4 and fwd % 256 == 0
+    assert bwd > fwd and bwd % 256 == 0
+    assert lib.kan_workspace_bytes(None, 1, 0) == 0
+    bad = binding.KanLayerDesc(512, 512, 0, 3, -1.0, 1.0, 1)
+    assert lib.kan_workspace_bytes(ctypes.byref(bad), 1, 0) == 0
+    lib.ukan_workspace_bytes.restype = ctypes.c_size_t
+    lib.ukan_workspace_bytes.argtypes = [ctypes.POINTER(binding.UkanLayerDesc), ctypes.c_int64, ctypes.c_int32,
+                                         ctypes.c_int]
+    u = binding.UkanLayerDesc(128, 256, 3, 0.25, 32, 32, 64, 0)
+    assert lib.ukan_workspace_bytes(ctypes.byref(u), 32768, 128, 1) > lib.ukan_workspace_bytes(
+        ctypes.byref(u), 32768, 128, 0) > 128 * 128 * 4 * 256 * 4
+    # B == 0 succeeds before any pointer is looked at; null descriptor is rejected
+    lib.kan_forward.restype = ctypes.c_int
+    assert lib.kan_forward(ctypes.byref(d), ctypes.c_int64(0), None, None, None, None, None, None,
+                           ctypes.c_size_t(0), None) == binding.KAN_OK
+    assert lib.kan_forward(None, ctypes.c_int64(0), None, None, None, None, None, None, ctypes.c_size_t(0),
+                           None) == binding.KAN_ERR_INVALID_ARG
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError):
+        binding.load()

@@ -26,6 +26,7 @@ SplineGeom geom_of(const kan_layer_desc *d)
     g.n_in = d->n_in;
     g.n_out = d->n_out;
     g.rows = d->G + d->k;
+    g.slab_rows = g.rows + 1;
     g.k = d->k;
     g.lo = d->grid_lo;
     g.inv_h = (float)d->G / (d->grid_hi - d->grid_lo);
@@ -34,9 +35,10 @@ SplineGeom geom_of(const kan_layer_desc *d)
     return g;
 }
 
+// scale-folded table: G + k coefficient rows plus the w_b row per input
 size_t folded_bytes(const kan_layer_desc *d)
 {
-    return align_up((size_t)d->n_in * (size_t)(d->G + d->k) * (size_t)d->n_out * sizeof(float));
+    return align_up((size_t)d->n_in * (size_t)(d->G + d->k + 1) * (size_t)d->n_out * sizeof(float));
 }
 
 size_t edge_bytes(const kan_layer_desc *d)
@@ -83,9 +85,10 @@ extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x
     hipStream_t st = (hipStream_t)stream;
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
-    if (launch_fold_scale(coef, w_s, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
-    if (launch_forward_generic(g, x, cf, w_b, y, B, st) != hipSuccess) return KAN_ERR_HIP;
-    return KAN_OK;
+    if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
+    hipError_t e = forward_lds_plan(g) ? launch_forward_lds(g, x, cf, y, B, st)
+                                       : launch_forward_generic(g, x, cf, w_b, y, B, st);
+    return e == hipSuccess ? KAN_OK : KAN_ERR_HIP;
 }
 
 extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
@@ -105,7 +108,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     if (!dparam_generic_supported(g.rows) && (gcoef || gw_s || gw_b)) return KAN_ERR_UNSUPPORTED;
     float *cf = (float *)ws;
     if (gx) {
-        if (launch_fold_scale(coef, w_s, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
+        if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
         if (launch_dx_generic(g, x, cf, w_b, gy, gx, B, st) != hipSuccess) return KAN_ERR_HIP;
     }
     const bool want_b = gw_b && desc->base_act != KAN_BASE_NONE;

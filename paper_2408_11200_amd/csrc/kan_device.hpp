@@ -21,6 +21,8 @@ constexpr int kWave = 64;
 struct SplineGeom {
     int n_in, n_out;
     int rows;                  // coefficient rows per input
+    int slab_rows;             // rows per input in the scale-folded table: rows, or rows + 1 when
+                               // the table carries w_b as an extra last row
     int k;                     // degree
     float lo, inv_h;           // grid start and reciprocal cell width
     const int32_t *cell_base;  // per input, or nullptr (== 0)

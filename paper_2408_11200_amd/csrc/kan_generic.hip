@@ -58,17 +58,26 @@ __global__ void interval_index_kernel(const float *__restrict__ x, int32_t *__re
 }
 
 // ---- fold the per-edge spline scale into the coefficients -------------------
-// cf[i][m][j] = w_s[i][j] * coef[i][m][j]; afterwards the spline term costs K
-// multiply-adds per edge with no separate scale.
+// cf[i][m][j] = w_s[i][j] * coef[i][m][j] for m < rows, and cf[i][rows][j] = w_b[i][j] (zero without
+// a base term): afterwards the spline term costs K multiply-adds per edge with no separate scale,
+// and one input's operands are one contiguous (rows + 1) x n_out block.
 __global__ void fold_scale_kernel(const float *__restrict__ coef, const float *__restrict__ w_s,
-                                  float *__restrict__ cf, int n_in, int rows, int n_out)
+                                  const float *__restrict__ w_b, float *__restrict__ cf, int n_in, int rows,
+                                  int n_out)
 {
-    int64_t total = (int64_t)n_in * rows * n_out;
+    const int64_t per_in = (int64_t)(rows + 1) * n_out;
+    const int64_t total = (int64_t)n_in * per_in;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total;
          p += (int64_t)gridDim.x * blockDim.x) {
-        int j = (int)(p % n_out);
-        int i = (int)(p / ((int64_t)rows * n_out));
-        cf[p] = coef[p] * w_s[(int64_t)i * n_out + j];
+        const int i = (int)(p / per_in);
+        const int64_t rem = p - (int64_t)i * per_in;
+        const int m = (int)(rem / n_out), j = (int)(rem % n_out);
+        float v;
+        if (m < rows)
+            v = coef[((int64_t)i * rows + m) * n_out + j] * w_s[(int64_t)i * n_out + j];
+        else
+            v = w_b ? w_b[(int64_t)i * n_out + j] : 0.0f;
+        cf[p] = v;
     }
 }
 
@@ -116,7 +125,7 @@ __global__ __launch_bounds__(256) void forward_generic_kernel(SplineGeom g, cons
 
         const int n_ii = (g.n_in - i0 < IPV) ? g.n_in - i0 : IPV;
         for (int ii = 0; ii < n_ii; ++ii) {
-            const float *slab = cf + (int64_t)(i0 + ii) * g.rows * g.n_out + jc;
+            const float *slab = cf + (int64_t)(i0 + ii) * g.slab_rows * g.n_out + jc;
             float wb[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) wb[r] = 0.0f;
@@ -218,7 +227,7 @@ __global__ __launch_bounds__(256) void dx_generic_kernel(SplineGeom g, const flo
 #pragma unroll
             for (int ii = 0; ii < IPV; ++ii) {
                 if (i0 + ii < g.n_in) {
-                    const float *slab = cf + (int64_t)(i0 + ii) * g.rows * g.n_out + jc;
+                    const float *slab = cf + (int64_t)(i0 + ii) * g.slab_rows * g.n_out + jc;
                     float wb[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) wb[r] = 0.0f;
@@ -384,14 +393,14 @@ hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float 
     return hipGetLastError();
 }
 
-hipError_t launch_fold_scale(const float *coef, const float *w_s, float *cf, int n_in, int rows, int n_out,
-                             hipStream_t st)
+hipError_t launch_fold_scale(const float *coef, const float *w_s, const float *w_b, float *cf, int n_in, int rows,
+                             int n_out, hipStream_t st)
 {
-    int64_t total = (int64_t)n_in * rows * n_out;
+    int64_t total = (int64_t)n_in * (rows + 1) * n_out;
     int64_t want = (total + 255) / 256;
     unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
     prof::Timed tm("fold_scale", st);
-    fold_scale_kernel<<<blocks, 256, 0, st>>>(coef, w_s, cf, n_in, rows, n_out);
+    fold_scale_kernel<<<blocks, 256, 0, st>>>(coef, w_s, w_b, cf, n_in, rows, n_out);
     return hipGetLastError();
 }
 

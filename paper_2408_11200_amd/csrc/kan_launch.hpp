@@ -24,8 +24,8 @@ struct Timed {
 
 hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float lo, float inv_h,
                                  hipStream_t st);
-hipError_t launch_fold_scale(const float *coef, const float *w_s, float *cf, int n_in, int rows, int n_out,
-                             hipStream_t st);
+hipError_t launch_fold_scale(const float *coef, const float *w_s, const float *w_b, float *cf, int n_in, int rows,
+                             int n_out, hipStream_t st);
 
 // generic (any shape) kernels
 hipError_t launch_forward_generic(const SplineGeom &g, const float *x, const float *cf, const float *w_b,
@@ -38,6 +38,11 @@ hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const floa
 hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const float *coef, const float *w_s,
                                 float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
                                 int n_chunks, hipStream_t st);
+
+// LDS-staged kernels (small grids); *_plan returns 0 when the shape does not qualify
+int forward_lds_plan(const SplineGeom &g);
+hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
+                              hipStream_t st);
 
 // How the batch is cut into chunks for the parameter-gradient reduction: chunks of about 1024
 // samples, at most 64 of them, and no more than fit a 512 MiB budget of partial sums.

@@ -117,7 +117,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
 
     SplineGeom &g = out->g;
     g.n_in = d->n_in; g.n_out = d->n_out;
-    g.rows = span * K; g.k = d->k;
+    g.rows = span * K; g.slab_rows = g.rows; g.k = d->k;
     g.lo = 0.0f; g.inv_h = inv_h;
     g.cell_base = cell_base;
     g.base_act = d->base_act;

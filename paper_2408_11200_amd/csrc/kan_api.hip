@@ -46,6 +46,28 @@ size_t edge_bytes(const kan_layer_desc *d)
     return align_up((size_t)d->n_in * (size_t)d->n_out * sizeof(float));
 }
 
+// which kernels the backward pass uses and how its scratch is cut
+struct BackwardPlan {
+    bool sorted;
+    ChunkPlan cp;
+    size_t rec_bytes;       // one record array (0 for the generic path)
+};
+
+BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
+{
+    SplineGeom g = geom_of(d);
+    BackwardPlan bp;
+    bp.sorted = backward_sorted_applicable(g) != 0;
+    if (bp.sorted) {
+        bp.cp = plan_chunks_sorted(B, g.n_in, g.rows, g.n_out, dparam_sorted_waves(g.rows));
+        bp.rec_bytes = align_up(pair_record_bytes(B, g.n_in));
+    } else {
+        bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
+        bp.rec_bytes = 0;
+    }
+    return bp;
+}
+
 }  // namespace
 
 extern "C" const char *kan_strerror(int status)
@@ -66,8 +88,8 @@ extern "C" size_t kan_workspace_bytes(const kan_layer_desc *desc, int64_t B, int
     if (check_desc(desc) != KAN_OK || B < 0) return 0;
     if (pass == KAN_PASS_FORWARD) return folded_bytes(desc);
     if (pass != KAN_PASS_BACKWARD) return 0;
-    ChunkPlan cp = plan_chunks(B, desc->n_in, desc->G + desc->k, desc->n_out);
-    return folded_bytes(desc) + (size_t)cp.n_chunks * (folded_bytes(desc) + edge_bytes(desc));
+    const BackwardPlan bp = backward_plan(desc, B);
+    return folded_bytes(desc) + bp.rec_bytes + (size_t)bp.cp.n_chunks * (folded_bytes(desc) + edge_bytes(desc));
 }
 
 extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
@@ -105,7 +127,8 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         return KAN_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     SplineGeom g = geom_of(desc);
-    if (!dparam_generic_supported(g.rows) && (gcoef || gw_s || gw_b)) return KAN_ERR_UNSUPPORTED;
+    if (!backward_sorted_applicable(g) && !dparam_generic_supported(g.rows) && (gcoef || gw_s || gw_b))
+        return KAN_ERR_UNSUPPORTED;
     float *cf = (float *)ws;
     if (gx) {
         if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
@@ -113,12 +136,21 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     }
     const bool want_b = gw_b && desc->base_act != KAN_BASE_NONE;
     if (gcoef || gw_s || gw_b) {
-        ChunkPlan cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
-        float *part_c = (float *)((char *)ws + folded_bytes(desc));
+        const BackwardPlan bp = backward_plan(desc, B);
+        const ChunkPlan cp = bp.cp;
+        char *at = (char *)ws + folded_bytes(desc);
+        PairRecord *rec_w = (PairRecord *)at;
+        at += bp.rec_bytes;
+        float *part_c = (float *)at;
         float *part_b = (float *)((char *)part_c + (size_t)cp.n_chunks * folded_bytes(desc));
         // partial slabs are laid out back to back with the unpadded slab size
-        if (launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
-                                  st) != hipSuccess)
+        if (bp.sorted) {
+            if (launch_pair_records(g, x, B, rec_w, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
+            if (launch_dparam_sorted(g, rec_w, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
+                                     st) != hipSuccess)
+                return KAN_ERR_HIP;
+        } else if (launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
+                                         st) != hipSuccess)
             return KAN_ERR_HIP;
         if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
                                  g.n_out, cp.n_chunks, st) != hipSuccess)

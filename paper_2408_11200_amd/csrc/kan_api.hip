@@ -132,7 +132,9 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     float *cf = (float *)ws;
     if (gx) {
         if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
-        if (launch_dx_generic(g, x, cf, w_b, gy, gx, B, st) != hipSuccess) return KAN_ERR_HIP;
+        hipError_t e = dx_lds_plan(g) ? launch_dx_lds(g, x, cf, gy, gx, B, st)
+                                      : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
+        if (e != hipSuccess) return KAN_ERR_HIP;
     }
     const bool want_b = gw_b && desc->base_act != KAN_BASE_NONE;
     if (gcoef || gw_s || gw_b) {

@@ -44,6 +44,10 @@ int forward_lds_plan(const SplineGeom &g);
 hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
                               hipStream_t st);
 
+int dx_lds_plan(const SplineGeom &g);
+hipError_t launch_dx_lds(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx, int64_t B,
+                         hipStream_t st);
+
 // Record-driven kernels (small grids).  One record per (sample, input) pair, stored
 // [tile of 64 samples][input][rank by window row]: first window row, sample index in the tile, the K window weights (or their x-derivatives) and the base value
 // (or derivative).

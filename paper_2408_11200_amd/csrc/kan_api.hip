@@ -51,6 +51,7 @@ struct BackwardPlan {
     bool sorted;
     ChunkPlan cp;
     size_t rec_bytes;       // one record array (0 for the generic path)
+    int b_slices_per_chunk; // base-term partial slices each chunk writes
 };
 
 BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
@@ -61,9 +62,11 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     if (bp.sorted) {
         bp.cp = plan_chunks_sorted(B, g.n_in, g.rows, g.n_out, dparam_sorted_waves(g.rows));
         bp.rec_bytes = align_up(pair_record_bytes(B, g.n_in));
+        bp.b_slices_per_chunk = 1;
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
         bp.rec_bytes = 0;
+        bp.b_slices_per_chunk = dparam_generic_row_blocks(g.rows);
     }
     return bp;
 }
@@ -89,7 +92,8 @@ extern "C" size_t kan_workspace_bytes(const kan_layer_desc *desc, int64_t B, int
     if (pass == KAN_PASS_FORWARD) return folded_bytes(desc);
     if (pass != KAN_PASS_BACKWARD) return 0;
     const BackwardPlan bp = backward_plan(desc, B);
-    return folded_bytes(desc) + bp.rec_bytes + (size_t)bp.cp.n_chunks * (folded_bytes(desc) + edge_bytes(desc));
+    return folded_bytes(desc) + bp.rec_bytes + (size_t)bp.cp.n_chunks * folded_bytes(desc) +
+           (size_t)bp.cp.n_chunks * bp.b_slices_per_chunk * edge_bytes(desc);
 }
 
 extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
@@ -127,8 +131,6 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         return KAN_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     SplineGeom g = geom_of(desc);
-    if (!backward_sorted_applicable(g) && !dparam_generic_supported(g.rows) && (gcoef || gw_s || gw_b))
-        return KAN_ERR_UNSUPPORTED;
     float *cf = (float *)ws;
     if (gx) {
         if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
@@ -155,7 +157,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
                                          st) != hipSuccess)
             return KAN_ERR_HIP;
         if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
-                                 g.n_out, cp.n_chunks, st) != hipSuccess)
+                                 g.n_out, cp.n_chunks, cp.n_chunks * bp.b_slices_per_chunk, st) != hipSuccess)
             return KAN_ERR_HIP;
     }
     return KAN_OK;

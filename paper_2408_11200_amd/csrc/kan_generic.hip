@@ -273,30 +273,39 @@ __global__ __launch_bounds__(256) void dx_generic_kernel(SplineGeom g, const flo
 }
 
 // ---- backward: parameter gradients -------------------------------------------
-// Stage 1.  One wave owns input i, a tile of 64*R outputs and one chunk of the
-// batch, and keeps
-//   acc[m][j] = sum_{b in chunk} gy[b][j] * N_{m - cell(b,i)}(u(b,i))
-// in LDS that only this wave touches; samples are visited in index order, so the
-// sum order is fixed.  The raw sums go to part_c[chunk][i][m][j] and the base-term
-// sums  sum_b gy[b][j] * silu(x[b][i])  to part_b[chunk][i][j].
+// Stage 1.  One wave owns input i, a tile of 64*R outputs, one block of kRowBlock coefficient rows
+// and one chunk of the batch, and keeps
+//   acc[m][j] = sum_{b in chunk} gy[b][j] * N_{m - cell(b,i)}(u(b,i))      (m in its row block)
+// in LDS that only this wave touches.  Samples are visited in index order and every row has exactly
+// one owner, so the sum order is fixed.  Samples whose window misses the row block are skipped with
+// a scalar test, which is what keeps large grids cheap: the LDS footprint per wave is a row block,
+// not the whole slab, so many waves fit on a CU.  The raw sums go to part_c[chunk][i][m][j]; the
+// base-term sums  sum_b gy[b][j] * silu(x[b][i])  are taken by the block that owns the sample's
+// clamped cell and go to part_b[chunk * n_row_blocks + block][i][j].
+constexpr int kRowBlock = 16;
+
 template <int R>
 __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const float *__restrict__ x,
                                                             const float *__restrict__ gy,
                                                             float *__restrict__ part_c,
                                                             float *__restrict__ part_b, int64_t B,
-                                                            int64_t chunk_len)
+                                                            int64_t chunk_len, int n_jt)
 {
-    extern __shared__ float acc[];          // [rows][64*R]
     constexpr int TJ = kWave * R;
+    __shared__ float acc[kRowBlock * TJ];
     const int lane = threadIdx.x;
     const int i = blockIdx.x;
-    const int j = blockIdx.y * TJ + lane * R;
+    const int jt = blockIdx.y % n_jt, rb = blockIdx.y / n_jt;
+    const int n_rb = gridDim.y / n_jt;
+    const int lo = rb * kRowBlock;
+    const int hi = (lo + kRowBlock < g.rows) ? lo + kRowBlock : g.rows;
+    const int j = jt * TJ + lane * R;
     const bool j_ok = j < g.n_out;
     const int jc = j_ok ? j : 0;
     const int64_t b_lo = (int64_t)blockIdx.z * chunk_len;
     const int64_t b_hi = (b_lo + chunk_len < B) ? b_lo + chunk_len : B;
 
-    for (int m = 0; m < g.rows; ++m)
+    for (int m = 0; m < kRowBlock; ++m)
 #pragma unroll
         for (int r = 0; r < R; ++r) acc[m * TJ + lane * R + r] = 0.0f;
     float accb[R];
@@ -308,19 +317,26 @@ __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const 
         Pair p = pair_eval<false>(x[my_b * g.n_in + i], g, i);
         const int n_b = (b_hi - b0 < kWave) ? (int)(b_hi - b0) : kWave;
         for (int t = 0; t < n_b; ++t) {
+            const int cell = lane_i(p.cell, t);
+            const int owner = clampi(cell, 0, g.rows - 1);
+            const bool touches = cell + kMaxK > lo && cell < hi;
+            const bool owns = owner >= lo && owner < hi;
+            if (!(touches || (owns && part_b))) continue;          // uniform
             float gv[R];
             load_vec<R>(gy + (b0 + t) * g.n_out + jc, gv);
-            const int cell = lane_i(p.cell, t);
-            if (cell > -kMaxK && cell < g.rows) {
+            if (touches) {
 #pragma unroll
                 for (int s = 0; s < kMaxK; ++s) {
-                    const float ws = lane_f(p.w[s], t);
-                    float *row = acc + clampi(cell + s, 0, g.rows - 1) * TJ + lane * R;
+                    const int m = cell + s;
+                    if (m >= lo && m < hi) {                        // uniform
+                        const float ws = lane_f(p.w[s], t);
+                        float *row = acc + (m - lo) * TJ + lane * R;
 #pragma unroll
-                    for (int r = 0; r < R; ++r) row[r] = fmaf(ws, gv[r], row[r]);
+                        for (int r = 0; r < R; ++r) row[r] = fmaf(ws, gv[r], row[r]);
+                    }
                 }
             }
-            if (g.base_act) {
+            if (owns && part_b) {
                 const float bs = lane_f(p.base, t);
 #pragma unroll
                 for (int r = 0; r < R; ++r) accb[r] = fmaf(bs, gv[r], accb[r]);
@@ -329,16 +345,17 @@ __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const 
     }
     if (!j_ok) return;
     float *pc = part_c + ((int64_t)blockIdx.z * g.n_in + i) * g.rows * g.n_out + j;
-    for (int m = 0; m < g.rows; ++m) {
+    for (int m = lo; m < hi; ++m) {
         float a[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) a[r] = acc[m * TJ + lane * R + r];
+        for (int r = 0; r < R; ++r) a[r] = acc[(m - lo) * TJ + lane * R + r];
         store_vec<R>(pc + (int64_t)m * g.n_out, a);
     }
-    if (part_b) store_vec<R>(part_b + ((int64_t)blockIdx.z * g.n_in + i) * g.n_out + j, accb);
+    if (part_b) store_vec<R>(part_b + (((int64_t)blockIdx.z * n_rb + rb) * g.n_in + i) * g.n_out + j, accb);
 }
 
-// Stage 2.  Sum the per-chunk partial sums in chunk order (fp64 accumulator, so the
+// Stage 2.  Sum the partial sums (n_chunks slabs for the coefficient rows, n_slices_b slices for the
+// base term) in order (fp64 accumulator, so the
 // long batch sum costs no accuracy) and turn them into the three gradients:
 //   gcoef = w_s * acc,   gw_s = sum_m coef * acc,   gw_b = base sums.
 // One thread per (input, output); consecutive threads read consecutive outputs.
@@ -348,7 +365,7 @@ __global__ __launch_bounds__(256) void dparam_reduce_kernel(const float *__restr
                                                             const float *__restrict__ w_s,
                                                             float *__restrict__ gcoef, float *__restrict__ gw_s,
                                                             float *__restrict__ gw_b, int n_in, int rows,
-                                                            int n_out, int n_chunks)
+                                                            int n_out, int n_chunks, int n_slices_b)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)n_in * n_out) return;
@@ -369,7 +386,7 @@ __global__ __launch_bounds__(256) void dparam_reduce_kernel(const float *__restr
     if (gw_b) {
         double a = 0.0;
         if (part_b)      // no base term: the gradient is identically zero
-            for (int c = 0; c < n_chunks; ++c) a += (double)part_b[(int64_t)c * n_in * n_out + e];
+            for (int c = 0; c < n_slices_b; ++c) a += (double)part_b[(int64_t)c * n_in * n_out + e];
         gw_b[e] = (float)a;
     }
 }
@@ -446,47 +463,33 @@ hipError_t launch_dx_generic(const SplineGeom &g, const float *x, const float *c
     }
 }
 
-// LDS bytes one dparam wave needs; the launcher lowers R until the tile fits.
-static size_t dparam_lds(int rows, int R) { return (size_t)rows * 64 * R * sizeof(float); }
-
-int dparam_generic_supported(int rows) { return dparam_lds(rows, 1) <= 160 * 1024 ? 1 : 0; }
+int dparam_generic_row_blocks(int rows) { return (rows + kRowBlock - 1) / kRowBlock; }
 
 hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const float *gy, float *part_c,
                                  float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st)
 {
-    int R = pick_r(g.n_out);
-    while (R > 1 && dparam_lds(g.rows, R) > 48 * 1024) R /= 2;
-    size_t lds = dparam_lds(g.rows, R);
-    dim3 grid((unsigned)g.n_in, (unsigned)((g.n_out + 64 * R - 1) / (64 * R)), (unsigned)n_chunks);
-    hipError_t e = hipSuccess;
+    const int R = pick_r(g.n_out);
+    const int n_jt = (g.n_out + 64 * R - 1) / (64 * R);
+    const int n_rb = dparam_generic_row_blocks(g.rows);
+    dim3 grid((unsigned)g.n_in, (unsigned)(n_jt * n_rb), (unsigned)n_chunks);
     prof::Timed tm("dparam_generic", st);
     switch (R) {
-    case 4:
-        dparam_generic_kernel<4><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
-        break;
-    case 2:
-        dparam_generic_kernel<2><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
-        break;
-    default:
-        if (lds > 64 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dparam_generic_kernel<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        dparam_generic_kernel<1><<<grid, 64, lds, st>>>(g, x, gy, part_c, part_b, B, chunk_len);
-        break;
+    case 4: dparam_generic_kernel<4><<<grid, 64, 0, st>>>(g, x, gy, part_c, part_b, B, chunk_len, n_jt); break;
+    case 2: dparam_generic_kernel<2><<<grid, 64, 0, st>>>(g, x, gy, part_c, part_b, B, chunk_len, n_jt); break;
+    default: dparam_generic_kernel<1><<<grid, 64, 0, st>>>(g, x, gy, part_c, part_b, B, chunk_len, n_jt); break;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const float *coef, const float *w_s,
                                 float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
-                                int n_chunks, hipStream_t st)
+                                int n_chunks, int n_slices_b, hipStream_t st)
 {
     int64_t total = (int64_t)n_in * n_out;
     prof::Timed tm("dparam_reduce", st);
     dparam_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part_c, part_b, coef, w_s, gcoef, gw_s,
-                                                                        gw_b, n_in, rows, n_out, n_chunks);
+                                                                        gw_b, n_in, rows, n_out, n_chunks,
+                                                                        n_slices_b);
     return hipGetLastError();
 }
 

@@ -51,7 +51,7 @@ Layout make_layout(const ukan_layer_desc *d, int64_t n_g, int n_chunks, int pass
         L.pre = take(rows * dh * 4);
         L.raw = take(table);
         L.part_c = take((size_t)n_chunks * table);
-        L.part_b = take((size_t)n_chunks * n_in * n_out * 4);
+        L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);
         L.gout = take(table);
         L.gpre = take(rows * dh * 4);
         size_t s1 = (size_t)split_slices((int64_t)rows) * dh * n_o * 4;      // gW2 partials
@@ -185,7 +185,6 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     const bool cg_grads = g && (g->gE || g->gW1 || g->gb1 || g->gW2 || g->gb2);
     const bool want_b = g && g->gw_b && desc->base_act != KAN_BASE_NONE;
     if (!(cg_grads || (g && (g->gscale || g->gw_b)))) return KAN_OK;
-    if (!dparam_generic_supported(pr.g.rows)) return KAN_ERR_UNSUPPORTED;
 
     // table gradient: partial sums per batch chunk, then  gout = scale * sum,  gscale = sum_m raw * sum
     float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
@@ -195,7 +194,7 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
         return KAN_ERR_HIP;
     if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
                              cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,
-                             pr.cp.n_chunks, st) != hipSuccess)
+                             pr.cp.n_chunks, pr.cp.n_chunks * dparam_generic_row_blocks(pr.g.rows), st) != hipSuccess)
         return KAN_ERR_HIP;
     if (!cg_grads) return KAN_OK;
 

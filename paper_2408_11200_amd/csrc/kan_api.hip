@@ -48,7 +48,7 @@ size_t edge_bytes(const kan_layer_desc *d)
 
 // which kernels the backward pass uses and how its scratch is cut
 struct BackwardPlan {
-    bool sorted;
+    bool sorted, narrow;
     ChunkPlan cp;
     size_t rec_bytes;       // one record array (0 for the generic path)
     int b_slices_per_chunk; // base-term partial slices each chunk writes
@@ -58,7 +58,8 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
 {
     SplineGeom g = geom_of(d);
     BackwardPlan bp;
-    bp.sorted = backward_sorted_applicable(g) != 0;
+    bp.narrow = narrow_applicable(g) != 0;
+    bp.sorted = !bp.narrow && backward_sorted_applicable(g) != 0;
     if (bp.sorted) {
         bp.cp = plan_chunks_sorted(B, g.n_in, g.rows, g.n_out, dparam_sorted_waves(g.rows));
         bp.rec_bytes = align_up(pair_record_bytes(B, g.n_in));
@@ -66,7 +67,7 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
         bp.rec_bytes = 0;
-        bp.b_slices_per_chunk = dparam_generic_row_blocks(g.rows);
+        bp.b_slices_per_chunk = bp.narrow ? dparam_narrow_row_blocks(g.rows) : dparam_generic_row_blocks(g.rows);
     }
     return bp;
 }
@@ -112,8 +113,9 @@ extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
     if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
-    hipError_t e = forward_lds_plan(g) ? launch_forward_lds(g, x, cf, y, B, st)
-                                       : launch_forward_generic(g, x, cf, w_b, y, B, st);
+    hipError_t e = narrow_applicable(g)   ? launch_forward_narrow(g, x, cf, w_b, y, B, st)
+                   : forward_lds_plan(g) ? launch_forward_lds(g, x, cf, y, B, st)
+                                         : launch_forward_generic(g, x, cf, w_b, y, B, st);
     return e == hipSuccess ? KAN_OK : KAN_ERR_HIP;
 }
 
@@ -134,8 +136,9 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     float *cf = (float *)ws;
     if (gx) {
         if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
-        hipError_t e = dx_lds_plan(g) ? launch_dx_lds(g, x, cf, gy, gx, B, st)
-                                      : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
+        hipError_t e = narrow_applicable(g) ? launch_dx_narrow(g, x, cf, w_b, gy, gx, B, st)
+                       : dx_lds_plan(g)     ? launch_dx_lds(g, x, cf, gy, gx, B, st)
+                                            : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
         if (e != hipSuccess) return KAN_ERR_HIP;
     }
     const bool want_b = gw_b && desc->base_act != KAN_BASE_NONE;
@@ -151,6 +154,10 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         if (bp.sorted) {
             if (launch_pair_records(g, x, B, rec_w, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
             if (launch_dparam_sorted(g, rec_w, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
+                                     st) != hipSuccess)
+                return KAN_ERR_HIP;
+        } else if (bp.narrow) {
+            if (launch_dparam_narrow(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
                                      st) != hipSuccess)
                 return KAN_ERR_HIP;
         } else if (launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,

@@ -355,33 +355,44 @@ __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const 
 }
 
 // Stage 2.  Sum the partial sums (n_chunks slabs for the coefficient rows, n_slices_b slices for the
-// base term) in order (fp64 accumulator, so the
-// long batch sum costs no accuracy) and turn them into the three gradients:
+// base term) in order with an fp64 accumulator, so that the long batch sum costs no accuracy, and
+// turn them into the three gradients:
 //   gcoef = w_s * acc,   gw_s = sum_m coef * acc,   gw_b = base sums.
-// One thread per (input, output); consecutive threads read consecutive outputs.
-__global__ __launch_bounds__(256) void dparam_reduce_kernel(const float *__restrict__ part_c,
-                                                            const float *__restrict__ part_b,
-                                                            const float *__restrict__ coef,
-                                                            const float *__restrict__ w_s,
-                                                            float *__restrict__ gcoef, float *__restrict__ gw_s,
-                                                            float *__restrict__ gw_b, int n_in, int rows,
-                                                            int n_out, int n_chunks, int n_slices_b)
+// 2a: one thread per table element (input, row, output): the chunk sum, gcoef, and the summed
+//     acc written back over chunk 0 of part_c for 2b.
+__global__ __launch_bounds__(256) void dparam_reduce_rows_kernel(float *__restrict__ part_c,
+                                                                 const float *__restrict__ w_s,
+                                                                 float *__restrict__ gcoef, int n_in, int rows,
+                                                                 int n_out, int n_chunks, int keep_sum)
+{
+    const int64_t slab = (int64_t)n_in * rows * n_out;
+    const int64_t at = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (at >= slab) return;
+    double a = 0.0;
+    for (int c = 0; c < n_chunks; ++c) a += (double)part_c[c * slab + at];
+    const int j = (int)(at % n_out);
+    const int i = (int)(at / ((int64_t)rows * n_out));
+    if (gcoef) gcoef[at] = (float)((double)w_s[(int64_t)i * n_out + j] * a);
+    if (keep_sum) part_c[at] = (float)a;
+}
+
+// 2b: one thread per (input, output): gw_s from the summed acc, gw_b from the base slices.
+__global__ __launch_bounds__(256) void dparam_reduce_edges_kernel(const float *__restrict__ acc_sum,
+                                                                  const float *__restrict__ part_b,
+                                                                  const float *__restrict__ coef,
+                                                                  float *__restrict__ gw_s, float *__restrict__ gw_b,
+                                                                  int n_in, int rows, int n_out, int n_slices_b)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)n_in * n_out) return;
     const int i = (int)(e / n_out), j = (int)(e % n_out);
-    const int64_t slab = (int64_t)n_in * rows * n_out;
-    const float ws = w_s[e];
-    double gws = 0.0;
-    if (gcoef || gw_s) {
+    if (gw_s) {
+        double s = 0.0;
         for (int m = 0; m < rows; ++m) {
             const int64_t at = ((int64_t)i * rows + m) * n_out + j;
-            double a = 0.0;
-            for (int c = 0; c < n_chunks; ++c) a += (double)part_c[c * slab + at];
-            if (gcoef) gcoef[at] = (float)((double)ws * a);
-            if (gw_s) gws += (double)coef[at] * a;
+            s += (double)coef[at] * (double)acc_sum[at];
         }
-        if (gw_s) gw_s[e] = (float)gws;
+        gw_s[e] = (float)s;
     }
     if (gw_b) {
         double a = 0.0;
@@ -481,15 +492,18 @@ hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const floa
     return hipGetLastError();
 }
 
-hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const float *coef, const float *w_s,
+hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float *coef, const float *w_s,
                                 float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
                                 int n_chunks, int n_slices_b, hipStream_t st)
 {
-    int64_t total = (int64_t)n_in * n_out;
+    const int64_t slab = (int64_t)n_in * rows * n_out, edges = (int64_t)n_in * n_out;
     prof::Timed tm("dparam_reduce", st);
-    dparam_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part_c, part_b, coef, w_s, gcoef, gw_s,
-                                                                        gw_b, n_in, rows, n_out, n_chunks,
-                                                                        n_slices_b);
+    if (gcoef || gw_s)
+        dparam_reduce_rows_kernel<<<(unsigned)((slab + 255) / 256), 256, 0, st>>>(part_c, w_s, gcoef, n_in, rows, n_out,
+                                                                                n_chunks, gw_s ? 1 : 0);
+    if (gw_s || gw_b)
+        dparam_reduce_edges_kernel<<<(unsigned)((edges + 255) / 256), 256, 0, st>>>(part_c, part_b, coef, gw_s, gw_b,
+                                                                                  n_in, rows, n_out, n_slices_b);
     return hipGetLastError();
 }
 

@@ -35,9 +35,19 @@ hipError_t launch_dx_generic(const SplineGeom &g, const float *x, const float *c
 int dparam_generic_row_blocks(int rows);     // base-term partial slices per chunk
 hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const float *gy, float *part_c,
                                  float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
-hipError_t launch_dparam_reduce(const float *part_c, const float *part_b, const float *coef, const float *w_s,
+hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float *coef, const float *w_s,
                                 float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
                                 int n_chunks, int n_slices_b, hipStream_t st);
+
+// narrow layers (n_out <= 16)
+int narrow_applicable(const SplineGeom &g);
+int dparam_narrow_row_blocks(int rows);
+hipError_t launch_forward_narrow(const SplineGeom &g, const float *x, const float *cf, const float *w_b, float *y,
+                                 int64_t B, hipStream_t st);
+hipError_t launch_dx_narrow(const SplineGeom &g, const float *x, const float *cf, const float *w_b, const float *gy,
+                            float *gx, int64_t B, hipStream_t st);
+hipError_t launch_dparam_narrow(const SplineGeom &g, const float *x, const float *gy, float *part_c, float *part_b,
+                                int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
 
 // LDS-staged kernels (small grids); *_plan returns 0 when the shape does not qualify
 int forward_lds_plan(const SplineGeom &g);

@@ -51,7 +51,7 @@ Layout make_layout(const ukan_layer_desc *d, int64_t n_g, int n_chunks, int pass
         L.pre = take(rows * dh * 4);
         L.raw = take(table);
         L.part_c = take((size_t)n_chunks * table);
-        L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);
+        L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);   // >= the narrow kernel's slice count
         L.gout = take(table);
         L.gpre = take(rows * dh * 4);
         size_t s1 = (size_t)split_slices((int64_t)rows) * dh * n_o * 4;      // gW2 partials
@@ -158,8 +158,10 @@ extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const flo
     Prepared pr;
     rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr);
     if (rc != KAN_OK) return rc;
-    if (launch_forward_generic(pr.g, x, (const float *)((char *)ws + pr.L.cf), p->w_b, y, B, st) != hipSuccess)
-        return KAN_ERR_HIP;
+    const float *cf = (const float *)((char *)ws + pr.L.cf);
+    hipError_t e = narrow_applicable(pr.g) ? launch_forward_narrow(pr.g, x, cf, p->w_b, y, B, st)
+                                           : launch_forward_generic(pr.g, x, cf, p->w_b, y, B, st);
+    if (e != hipSuccess) return KAN_ERR_HIP;
     return KAN_OK;
 }
 
@@ -179,8 +181,12 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     const int K = desc->k + 1, dh = desc->d_hidden, dz = desc->d_feat + desc->d_pe;
     const int64_t rows = (int64_t)desc->n_in * pr.n_g, n_o = (int64_t)K * desc->n_out;
 
-    if (gx && launch_dx_generic(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st) != hipSuccess)
-        return KAN_ERR_HIP;
+    const bool narrow = narrow_applicable(pr.g) != 0;
+    if (gx) {
+        hipError_t e = narrow ? launch_dx_narrow(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st)
+                              : launch_dx_generic(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st);
+        if (e != hipSuccess) return KAN_ERR_HIP;
+    }
 
     const bool cg_grads = g && (g->gE || g->gW1 || g->gb1 || g->gW2 || g->gb2);
     const bool want_b = g && g->gw_b && desc->base_act != KAN_BASE_NONE;
@@ -189,12 +195,18 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     // table gradient: partial sums per batch chunk, then  gout = scale * sum,  gscale = sum_m raw * sum
     float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
     float *gout = (float *)(w + L.gout);
-    if (launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks, pr.cp.chunk_len,
-                              st) != hipSuccess)
-        return KAN_ERR_HIP;
+    {
+        hipError_t e = narrow ? launch_dparam_narrow(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B,
+                                                     pr.cp.n_chunks, pr.cp.chunk_len, st)
+                              : launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B,
+                                                      pr.cp.n_chunks, pr.cp.chunk_len, st);
+        if (e != hipSuccess) return KAN_ERR_HIP;
+    }
+    const int b_slices = pr.cp.n_chunks * (narrow ? dparam_narrow_row_blocks(pr.g.rows)
+                                                  : dparam_generic_row_blocks(pr.g.rows));
     if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
                              cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,
-                             pr.cp.n_chunks, pr.cp.n_chunks * dparam_generic_row_blocks(pr.g.rows), st) != hipSuccess)
+                             pr.cp.n_chunks, b_slices, st) != hipSuccess)
         return KAN_ERR_HIP;
     if (!cg_grads) return KAN_OK;
 

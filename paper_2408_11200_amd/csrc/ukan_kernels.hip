@@ -265,22 +265,25 @@ __global__ __launch_bounds__(256) void slice_sum_kernel(const float *__restrict_
     out[e] = (float)s;
 }
 
-// gE[i][f] = sum_t sum_c W1[f][c] * gpre[(i,t)][c]
+// gE[i][f] = sum_c W1[f][c] * S[i][c],  S[i][c] = sum_t gpre[(i,t)][c].  One block per input: the
+// column sums S (fp64, rows in order) go through LDS, then one thread per embedding feature.
 __global__ __launch_bounds__(256) void embed_grad_kernel(const float *__restrict__ W1, const float *__restrict__ gpre,
                                                          float *__restrict__ gE, int n_in, int n_g, int d_feat,
                                                          int d_hid)
 {
-    int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n_in * d_feat) return;
-    int i = e / d_feat, f = e % d_feat;
-    double s = 0.0;
-    for (int t = 0; t < n_g; ++t) {
-        const float *gp = gpre + ((int64_t)i * n_g + t) * d_hid;
-        float r = 0.0f;
-        for (int c = 0; c < d_hid; ++c) r = fmaf(W1[(int64_t)f * d_hid + c], gp[c], r);
-        s += (double)r;
+    extern __shared__ double colsum[];          // [d_hid]
+    const int i = blockIdx.x;
+    for (int c = threadIdx.x; c < d_hid; c += blockDim.x) {
+        double s = 0.0;
+        for (int t = 0; t < n_g; ++t) s += (double)gpre[((int64_t)i * n_g + t) * d_hid + c];
+        colsum[c] = s;
     }
-    gE[e] = (float)s;
+    __syncthreads();
+    for (int f = threadIdx.x; f < d_feat; f += blockDim.x) {
+        double s = 0.0;
+        for (int c = 0; c < d_hid; ++c) s += (double)W1[(int64_t)f * d_hid + c] * colsum[c];
+        gE[(int64_t)i * d_feat + f] = (float)s;
+    }
 }
 
 // ---- launchers ----------------------------------------------------------------------
@@ -358,7 +361,7 @@ hipError_t launch_embed_grad(const float *W1, const float *gpre, float *gE, int 
                              int d_hid, hipStream_t st)
 {
     prof::Timed tm("cg_embed_grad", st);
-    embed_grad_kernel<<<(n_in * d_feat + 255) / 256, 256, 0, st>>>(W1, gpre, gE, n_in, n_g, d_feat, d_hid);
+    embed_grad_kernel<<<n_in, 256, (size_t)d_hid * sizeof(double), st>>>(W1, gpre, gE, n_in, n_g, d_feat, d_hid);
     return hipGetLastError();
 }
 

@@ -63,7 +63,7 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     if (bp.sorted) {
         bp.cp = plan_chunks_sorted(B, g.n_in, g.rows, g.n_out, dparam_sorted_waves(g.rows));
         bp.rec_bytes = align_up(pair_record_bytes(B, g.n_in));
-        bp.b_slices_per_chunk = 1;
+        bp.b_slices_per_chunk = dparam_sorted_row_blocks(g.rows);
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
         bp.rec_bytes = 0;

@@ -68,6 +68,7 @@ struct PairRecord {
 };
 int backward_sorted_applicable(const SplineGeom &g);
 int dparam_sorted_waves(int rows);
+int dparam_sorted_row_blocks(int rows);
 size_t pair_record_bytes(int64_t B, int n_in);
 hipError_t launch_pair_records(const SplineGeom &g, const float *x, int64_t B, PairRecord *rec_w, PairRecord *rec_d,
                             hipStream_t st);
@@ -102,7 +103,8 @@ inline ChunkPlan plan_chunks(int64_t B, int n_in, int rows, int n_out)
 inline ChunkPlan plan_chunks_sorted(int64_t B, int n_in, int rows, int n_out, int waves)
 {
     const int64_t tiles = (B + 63) / 64;
-    const int64_t wg_per_chunk = (int64_t)((n_in + waves - 1) / waves) * ((n_out + 255) / 256);
+    const int64_t items = (int64_t)n_in * dparam_sorted_row_blocks(rows);
+    const int64_t wg_per_chunk = ((items + waves - 1) / waves) * ((n_out + 255) / 256);
     int64_t n = (512 + wg_per_chunk - 1) / wg_per_chunk;
     const int64_t by_len = (B + 4095) / 4096;
     if (n < by_len) n = by_len;

@@ -102,26 +102,32 @@ __global__ __launch_bounds__(256) void pair_record_kernel(SplineGeom g, const fl
 }
 
 // ---- dL/dcoef, dL/dw_s, dL/dw_b: partial sums per batch chunk ---------------------------------
-// grid (ceil(n_in / NW), ceil(n_out / 256), chunks); block = NW waves, wave w owns input
-// blockIdx.x * NW + w and outputs j0 + 4*lane .. +3.  The gy tile (64 samples x 256 outputs) of the
-// current sample tile is shared through LDS, double-buffered.  acc[m] collects
-//   sum_b gy[b][j] * N_{m - row(b,i)}(u(b,i))   over the chunk, for every row m of the input,
-// in registers; the result goes to part_c[chunk][i][m][j] (and the base-term sums to part_b) for the
-// fixed-order fp64 reduction over chunks.
+// Work item = (input i, block of ROWS coefficient rows); a workgroup of NW waves takes NW consecutive
+// items (grid.x), one j-tile of 256 outputs (grid.y) and one chunk of the batch (grid.z).  The gy tile
+// (64 samples x 256 outputs) of the current sample tile is shared through LDS, double-buffered.
+// acc[m] collects   sum_b gy[b][j] * N_{m - row(b,i)}(u(b,i))   over the chunk for the rows
+// lo .. lo+ROWS-1 of the item, in registers.  A record whose window starts at row lo + d touches the
+// item's rows for d in -3 .. ROWS-1; because the records of a tile are sorted by row, those records are
+// one contiguous run (found with a ballot), and the run is walked with a loop that is statically
+// unrolled over d, so every accumulator index is a compile-time constant.  Results go to
+// part_c[chunk][i][m][j]; the base-term sums (taken by the item that holds the record's first row)
+// to part_b[chunk * blocks + block][i][j]; both are reduced over chunks in fixed order in fp64.
 template <int ROWS, int NW>
 __global__ __launch_bounds__(64 * NW) void dparam_sorted_kernel(SplineGeom g, const PairRecord *__restrict__ rec,
                                                                 const float *__restrict__ gy,
                                                                 float *__restrict__ part_c,
                                                                 float *__restrict__ part_b, int64_t B,
-                                                                int64_t tiles_per_chunk)
+                                                                int64_t tiles_per_chunk, int n_rb)
 {
     constexpr int TJ = 256, NT = 64 * NW;
     extern __shared__ float lds[];                      // 2 x [64][256]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int i = blockIdx.x * NW + wave;
-    const bool have_input = i < g.n_in;
-    const int ic = have_input ? i : g.n_in - 1;
+    const int item = blockIdx.x * NW + wave;
+    const bool have_item = item < g.n_in * n_rb;
+    const int i = have_item ? item / n_rb : g.n_in - 1;
+    const int rb = have_item ? item % n_rb : 0;
+    const int lo = rb * ROWS;
     const int j0 = blockIdx.y * TJ;
     const int j = j0 + lane * 4;
     const int64_t n_tiles = (B + kTile - 1) / kTile;
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(64 * NW) void dparam_sorted_kernel(SplineGeom g, co
     };
     copy_tile(tile_lo, lds);
     // this lane's record of the current tile; the next tile's is fetched while the current is used
-    PairRecord mine = rec[(tile_lo * g.n_in + ic) * kTile + lane];
+    PairRecord mine = rec[(tile_lo * g.n_in + i) * kTile + lane];
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -163,27 +169,39 @@ __global__ __launch_bounds__(64 * NW) void dparam_sorted_kernel(SplineGeom g, co
         float *nxt = lds + ((tile - tile_lo + 1) & 1) * (kTile * TJ);
         const int64_t tile_next = tile + 1 < tile_hi ? tile + 1 : tile;
         copy_tile(tile_next, nxt);
-        const PairRecord upcoming = rec[(tile_next * g.n_in + ic) * kTile + lane];
-        if (have_input) {
-            int pos = 0;
-            int rt = lane_i(mine.rt, 0);
+        const PairRecord upcoming = rec[(tile_next * g.n_in + i) * kTile + lane];
+        if (have_item) {
+            // the records whose window touches this item's rows: a contiguous run of the sorted list
+            const int r0 = mine.rt & 0xffff;
+            const unsigned long long hit = __ballot(r0 + kMaxK > lo && r0 < lo + ROWS);
+            if (hit) {
+                int pos = __builtin_ctzll(hit);
+                const int end = pos + __builtin_popcountll(hit);
+                int rt = lane_i(mine.rt, pos);
 #pragma unroll
-            for (int row = 0; row + kMaxK <= ROWS; ++row) {
-                while (pos < kTile && (rt & 0xffff) == row) {
-                    const float4 gv = *reinterpret_cast<const float4 *>(cur + (rt >> 16) * TJ);
-                    const float gr[4] = {gv.x, gv.y, gv.z, gv.w};
-                    float ws[kMaxK];
+                for (int d = 1 - kMaxK; d < ROWS; ++d) {        // window start relative to the item's rows
+                    while (pos < end && (rt & 0xffff) == lo + d) {
+                        const float4 gv = *reinterpret_cast<const float4 *>(cur + (rt >> 16) * TJ);
+                        const float gr[4] = {gv.x, gv.y, gv.z, gv.w};
+                        float ws[kMaxK];
 #pragma unroll
-                    for (int s = 0; s < kMaxK; ++s) ws[s] = lane_f(mine.w[s], pos);
-                    const float bs = lane_f(mine.base, pos);
-                    ++pos;
-                    rt = lane_i(mine.rt, pos & (kTile - 1));
+                        for (int s = 0; s < kMaxK; ++s) ws[s] = lane_f(mine.w[s], pos);
+                        const float bs = lane_f(mine.base, pos);
+                        ++pos;
+                        rt = lane_i(mine.rt, pos & (kTile - 1));
 #pragma unroll
-                    for (int s = 0; s < kMaxK; ++s)
+                        for (int s = 0; s < kMaxK; ++s) {
+                            if (d + s >= 0 && d + s < ROWS) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[row + s][r] = fmaf(ws[s], gr[r], acc[row + s][r]);
+                                for (int r = 0; r < 4; ++r)
+                                    acc[d + s < 0 ? 0 : d + s][r] = fmaf(ws[s], gr[r], acc[d + s < 0 ? 0 : d + s][r]);
+                            }
+                        }
+                        if (d >= 0) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) accb[r] = fmaf(bs, gr[r], accb[r]);
+                            for (int r = 0; r < 4; ++r) accb[r] = fmaf(bs, gr[r], accb[r]);
+                        }
+                    }
                 }
             }
         }
@@ -192,14 +210,15 @@ __global__ __launch_bounds__(64 * NW) void dparam_sorted_kernel(SplineGeom g, co
         __syncthreads();
     }
 
-    if (!have_input || j >= g.n_out) return;
+    if (!have_item || j >= g.n_out) return;
     float *pc = part_c + (((int64_t)blockIdx.z * g.n_in + i) * g.rows) * g.n_out + j;
 #pragma unroll
     for (int m = 0; m < ROWS; ++m)
-        if (m < g.rows)
-            *reinterpret_cast<float4 *>(pc + (int64_t)m * g.n_out) = make_float4(acc[m][0], acc[m][1], acc[m][2], acc[m][3]);
+        if (lo + m < g.rows)
+            *reinterpret_cast<float4 *>(pc + (int64_t)(lo + m) * g.n_out) =
+                make_float4(acc[m][0], acc[m][1], acc[m][2], acc[m][3]);
     if (part_b)
-        *reinterpret_cast<float4 *>(part_b + ((int64_t)blockIdx.z * g.n_in + i) * g.n_out + j) =
+        *reinterpret_cast<float4 *>(part_b + (((int64_t)blockIdx.z * n_rb + rb) * g.n_in + i) * g.n_out + j) =
             make_float4(accb[0], accb[1], accb[2], accb[3]);
 }
 
@@ -208,21 +227,21 @@ __global__ __launch_bounds__(64 * NW) void dparam_sorted_kernel(SplineGeom g, co
 int sorted_rows_template(int rows)
 {
     if (rows < kMaxK) return 0;
-    if (rows <= 16) return 16;
-    if (rows <= 24) return 24;
-    if (rows <= 32) return 32;
-    return 0;
+    return rows <= 16 ? 16 : 24;
 }
 
-int dparam_sorted_waves(int rows)
+// row blocks per input = base-term partial slices per chunk
+int dparam_sorted_row_blocks(int rows)
 {
     const int t = sorted_rows_template(rows);
-    return t == 32 ? 8 : 16;
+    return t ? (rows + t - 1) / t : 0;
 }
+
+int dparam_sorted_waves(int rows) { (void)rows; return 16; }
 
 int backward_sorted_applicable(const SplineGeom &g)
 {
-    return (sorted_rows_template(g.rows) != 0 && g.n_out % 4 == 0 && g.n_out >= 64) ? 1 : 0;
+    return (sorted_rows_template(g.rows) != 0 && g.rows <= 0xffff && g.n_out % 4 == 0 && g.n_out >= 64) ? 1 : 0;
 }
 
 size_t pair_record_bytes(int64_t B, int n_in)
@@ -250,9 +269,10 @@ static hipError_t dparam_sorted_launch(const SplineGeom &g, const PairRecord *re
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((g.n_in + NW - 1) / NW), (unsigned)((g.n_out + 255) / 256), (unsigned)n_chunks);
+    const int n_rb = (g.rows + ROWS - 1) / ROWS;
+    dim3 grid((unsigned)((g.n_in * n_rb + NW - 1) / NW), (unsigned)((g.n_out + 255) / 256), (unsigned)n_chunks);
     prof::Timed tm("dparam_sorted", st);
-    kern<<<grid, 64 * NW, lds, st>>>(g, rec, gy, part_c, part_b, B, chunk_len / kTile);
+    kern<<<grid, 64 * NW, lds, st>>>(g, rec, gy, part_c, part_b, B, chunk_len / kTile, n_rb);
     return hipGetLastError();
 }
 
@@ -263,7 +283,6 @@ hipError_t launch_dparam_sorted(const SplineGeom &g, const PairRecord *rec, cons
     switch (sorted_rows_template(g.rows)) {
     case 16: return dparam_sorted_launch<16, 16>(g, rec, gy, part_c, part_b, B, n_chunks, chunk_len, st);
     case 24: return dparam_sorted_launch<24, 16>(g, rec, gy, part_c, part_b, B, n_chunks, chunk_len, st);
-    case 32: return dparam_sorted_launch<32, 8>(g, rec, gy, part_c, part_b, B, n_chunks, chunk_len, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -27,13 +27,13 @@ int check_desc(const ukan_layer_desc *d)
 struct Layout {
     size_t cmin, cmax, g_first, n_groups, cell_base, summary;
     size_t hid, cf;                                   // forward
-    size_t z, pre, raw, part_c, part_b, gout, gpre, split;   // backward only
+    size_t z, pre, raw, rec, part_c, part_b, gout, gpre, split;   // backward only
     size_t total;
 };
 
 int split_slices(int64_t rows) { int64_t s = (rows + 511) / 512; return (int)(s < 1 ? 1 : (s > 64 ? 64 : s)); }
 
-Layout make_layout(const ukan_layer_desc *d, int64_t n_g, int n_chunks, int pass)
+Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunks, int pass)
 {
     const size_t K = (size_t)d->k + 1, n_in = (size_t)d->n_in, n_out = (size_t)d->n_out;
     const size_t rows = n_in * (size_t)n_g, n_o = K * n_out, dz = (size_t)d->d_feat + d->d_pe, dh = (size_t)d->d_hidden;
@@ -45,13 +45,14 @@ Layout make_layout(const ukan_layer_desc *d, int64_t n_g, int n_chunks, int pass
     L.n_groups = take(n_in * 4); L.cell_base = take(n_in * 4); L.summary = take(256);
     L.hid = take(rows * dh * 4);
     L.cf = take(table);
-    L.z = L.pre = L.raw = L.part_c = L.part_b = L.gout = L.gpre = L.split = 0;
+    L.z = L.pre = L.raw = L.rec = L.part_c = L.part_b = L.gout = L.gpre = L.split = 0;
     if (pass == KAN_PASS_BACKWARD) {
         L.z = take(rows * dz * 4);
         L.pre = take(rows * dh * 4);
         L.raw = take(table);
+        L.rec = take(pair_record_bytes(B, d->n_in));
         L.part_c = take((size_t)n_chunks * table);
-        L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);   // >= the narrow kernel's slice count
+        L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);   // >= the slice count of the other kernels
         L.gout = take(table);
         L.gpre = take(rows * dh * 4);
         size_t s1 = (size_t)split_slices((int64_t)rows) * dh * n_o * 4;      // gW2 partials
@@ -64,9 +65,14 @@ Layout make_layout(const ukan_layer_desc *d, int64_t n_g, int n_chunks, int pass
     return L;
 }
 
+// the record-driven kernel needs n_out % 4 == 0 and n_out >= 64; narrow layers have their own
+bool use_sorted(const ukan_layer_desc *d) { return d->n_out % 4 == 0 && d->n_out >= 64; }
+
 ChunkPlan chunks_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
-    return plan_chunks(B, d->n_in, max_groups * (d->k + 1), d->n_out);
+    const int rows = max_groups * (d->k + 1);
+    if (use_sorted(d)) return plan_chunks_sorted(B, d->n_in, rows, d->n_out, dparam_sorted_waves(rows));
+    return plan_chunks(B, d->n_in, rows, d->n_out);
 }
 
 struct Prepared {
@@ -83,7 +89,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     const int K = d->k + 1;
     const float inv_h = 1.0f / d->h;
     out->cp = chunks_for(d, B, max_groups);
-    Layout L0 = make_layout(d, max_groups, out->cp.n_chunks, pass);     // meta offsets do not depend on n_g
+    Layout L0 = make_layout(d, B, max_groups, out->cp.n_chunks, pass);     // meta offsets do not depend on n_g
     int32_t *cmin = (int32_t *)(ws + L0.cmin), *cmax = (int32_t *)(ws + L0.cmax);
     int32_t *g_first = (int32_t *)(ws + L0.g_first), *n_groups = (int32_t *)(ws + L0.n_groups);
     int32_t *cell_base = (int32_t *)(ws + L0.cell_base), *summary = (int32_t *)(ws + L0.summary);
@@ -94,7 +100,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     if (hipStreamSynchronize(st) != hipSuccess) return KAN_ERR_HIP;
     if (span < 2 || span > max_groups) return KAN_ERR_RANGE;
     out->n_g = span;
-    out->L = make_layout(d, span, out->cp.n_chunks, pass);
+    out->L = make_layout(d, B, span, out->cp.n_chunks, pass);
     const Layout &L = out->L;
     const int64_t rows = (int64_t)d->n_in * span;
     const int64_t n_o = (int64_t)K * d->n_out;
@@ -145,7 +151,7 @@ extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *desc, int64_t B, i
     if (check_desc(desc) != KAN_OK || B < 0 || max_groups < 2) return 0;
     if (pass != KAN_PASS_FORWARD && pass != KAN_PASS_BACKWARD) return 0;
     ChunkPlan cp = chunks_for(desc, B, max_groups);
-    return make_layout(desc, max_groups, cp.n_chunks, pass).total;
+    return make_layout(desc, B, max_groups, cp.n_chunks, pass).total;
 }
 
 extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
@@ -195,15 +201,24 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     // table gradient: partial sums per batch chunk, then  gout = scale * sum,  gscale = sum_m raw * sum
     float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
     float *gout = (float *)(w + L.gout);
-    {
+    const bool sorted = !narrow && use_sorted(desc) && backward_sorted_applicable(pr.g);
+    int b_slices;
+    if (sorted) {
+        PairRecord *rec = (PairRecord *)(w + L.rec);
+        if (launch_pair_records(pr.g, x, B, rec, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
+        if (launch_dparam_sorted(pr.g, rec, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,
+                                 pr.cp.chunk_len, st) != hipSuccess)
+            return KAN_ERR_HIP;
+        b_slices = pr.cp.n_chunks * dparam_sorted_row_blocks(pr.g.rows);
+    } else {
         hipError_t e = narrow ? launch_dparam_narrow(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B,
                                                      pr.cp.n_chunks, pr.cp.chunk_len, st)
                               : launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B,
                                                       pr.cp.n_chunks, pr.cp.chunk_len, st);
         if (e != hipSuccess) return KAN_ERR_HIP;
+        b_slices = pr.cp.n_chunks * (narrow ? dparam_narrow_row_blocks(pr.g.rows)
+                                            : dparam_generic_row_blocks(pr.g.rows));
     }
-    const int b_slices = pr.cp.n_chunks * (narrow ? dparam_narrow_row_blocks(pr.g.rows)
-                                                  : dparam_generic_row_blocks(pr.g.rows));
     if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
                              cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,
                              pr.cp.n_chunks, b_slices, st) != hipSuccess)

@@ -22,6 +22,14 @@ def flops_per_edge(k):
     return 2 * (k + 1) + 2
 
 
+# HBM-side bytes per launch on the config-3 workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
+# 1 GiB copy (profiles/kan_c3_fwd_bwd_hbm_traffic.md): read + written.  Only valid for that workload and these kernels.
+MEASURED_TRAFFIC_BYTES_C3 = {
+    "forward_lds": 235.3e6 + 33.6e6,
+    "dx_lds": 268.5e6 + 33.6e6,
+    "dparam_sorted": 469.9e6 + 201.3e6,
+}
+
 KERNEL_ROLE = {  # kernel family -> which third of the fwd+bwd work it carries
     "forward_generic": "forward", "dx_generic": "dx", "dparam_generic": "dparam",
     "forward_lds": "forward", "dx_lds": "dx", "dparam_sorted": "dparam",
@@ -35,6 +43,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
@@ -65,6 +75,14 @@ def main():
         binding.kan_forward(s, x, coef, w_s, w_b, y=y, ws=ws_f)
         binding.kan_backward(s, x, coef, w_s, w_b, gy, out=out, ws=ws_b)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -91,7 +109,8 @@ def main():
         flops, achieved = None, None
     peak = roofline.MI355X_FP32_VECTOR_FLOPS / 1e12
     rl = {"bound": "alu", "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-          "frac": (achieved / peak) if achieved else None, "traffic": None,
+          "frac": (achieved / peak) if achieved else None,
+          "traffic": MEASURED_TRAFFIC_BYTES_C3.get(dom) if args.workload == "c3" else None,
           "kernel_ms": dom_ms,
           "peak_unpacked": roofline.MI355X_FP32_VECTOR_FLOPS_UNPACKED / 1e12,
           "frac_unpacked": (achieved / (roofline.MI355X_FP32_VECTOR_FLOPS_UNPACKED / 1e12)) if achieved else None,

@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dense-baseline", action="store_true",
+                    help="also time the dense basis x coefficient GEMM formulation of the forward pass")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -117,6 +119,23 @@ def main():
           "whole_path_frac": roofline.algorithmic_flops_per_edge(s.k + 1) * value / roofline.MI355X_FP32_VECTOR_FLOPS,
           "kernels_ms": {n: round(v, 4) for n, v in sorted(avg.items())}}
 
+    dense = None
+    if args.dense_baseline:
+        ws_d = torch.empty(binding.load().kan_dense_baseline_workspace_bytes(binding.kan_desc(s), B), dtype=torch.uint8,
+                           device="cuda")
+        for _ in range(2):
+            binding.kan_dense_baseline_forward(s, x, coef, w_s, w_b, y=y, ws=ws_d)
+        torch.cuda.synchronize()
+        d0 = time.perf_counter()
+        for _ in range(5):
+            binding.kan_dense_baseline_forward(s, x, coef, w_s, w_b, y=y, ws=ws_d)
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - d0) * 1e3 / 5
+        fwd_ms = sum(v for n, v in avg.items() if KERNEL_ROLE.get(n) == "forward") + avg.get("fold_scale", 0.0)
+        dense = {"forward_ms_dense_gemm": dense_ms, "forward_ms_local": fwd_ms,
+                 "note": "forward pass only; dense = expand all G+k bases + rocBLAS sgemm"}
+        del ws_d
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -138,6 +157,8 @@ def main():
             "config": {"workload": w.name, "B": B, "n_in": s.n_in, "n_out": s.n_out, "G": s.G, "k": s.k,
                        "grid": [s.grid_lo, s.grid_hi], "pass": "forward+backward"},
             "roofline": rl, "cpu_baseline": cpu}
+    if dense:
+        line["dense_baseline"] = dense
     print(json.dumps(line))
     return 0
 

@@ -135,6 +135,16 @@ typedef struct kan_kernel_time {
 int kan_profile_enable(int on);
 int kan_profile_read(kan_kernel_time *out, int capacity);
 
+/* Comparison baseline, not the product path: the forward pass written as one dense GEMM
+   y = Phi * C over all G + k basis functions per input (the O(G) formulation of table "Complexity",
+   row "Torch KAN"), with Phi materialised in the workspace and the contraction done by rocBLAS.
+   Unlike every other entry point it creates a rocBLAS handle on first use (which allocates) and
+   keeps it for the life of the process. */
+size_t kan_dense_baseline_workspace_bytes(const kan_layer_desc *desc, int64_t B);
+int kan_dense_baseline_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                               const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
+                               void *stream);
+
 /* ---- UKAN ------------------------------------------------------------------------------ */
 
 /* Scratch bytes for ukan_cg_forward / ukan_cg_backward.  max_groups bounds, per input, the

@@ -21,7 +21,8 @@ KAN_ERR_HIP = -5
 PASS_FORWARD, PASS_BACKWARD = 0, 1
 
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
-           "kan_profile_enable", "kan_profile_read",
+           "kan_profile_enable", "kan_profile_read", "kan_dense_baseline_workspace_bytes",
+           "kan_dense_baseline_forward",
            "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_group_index"]
 
 
@@ -81,6 +82,10 @@ def load():
     lib.kan_profile_enable.argtypes = [ctypes.c_int]
     lib.kan_profile_read.restype = ctypes.c_int
     lib.kan_profile_read.argtypes = [ctypes.POINTER(KanKernelTime), ctypes.c_int]
+    lib.kan_dense_baseline_workspace_bytes.restype = sz
+    lib.kan_dense_baseline_workspace_bytes.argtypes = [ctypes.POINTER(KanLayerDesc), i64]
+    lib.kan_dense_baseline_forward.restype = ctypes.c_int
+    lib.kan_dense_baseline_forward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ukan_workspace_bytes.restype = sz
     lib.ukan_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i32, ctypes.c_int]
     lib.ukan_cg_forward.restype = ctypes.c_int
@@ -180,6 +185,22 @@ def kan_interval_index(spec, x, stream=None):
     if rc != KAN_OK:
         raise KanError(rc, "kan_interval_index")
     return idx
+
+
+def kan_dense_baseline_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=None):
+    """Comparison baseline: the same forward pass as one dense GEMM over all basis functions."""
+    lib = load()
+    d = kan_desc(spec)
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(lib.kan_dense_baseline_workspace_bytes(ctypes.byref(d), B), x.device)
+    rc = lib.kan_dense_baseline_forward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(y),
+                                        _ptr(ws), ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_dense_baseline_forward")
+    return y
 
 
 def kan_profile_enable(on):

@@ -1,0 +1,82 @@
+// Dense basis x coefficient baseline for the forward pass (comparison only, not the product path):
+// the layer written as one GEMM,  y = Phi * C,  Phi[b][i*(rows+1) + m] = B_{m,k}(x[b][i]) for m < rows
+// and silu(x[b][i]) for m = rows,  C = the scale-folded table [n_in*(rows+1)][n_out].
+// This is the O(G) formulation the local kernels avoid (Table "Complexity": Torch KAN vs Warp KAN);
+// it materialises Phi in the workspace and runs the contraction through rocBLAS on the matrix cores.
+#include <rocblas/rocblas.h>
+#include "kan.h"
+#include "kan_launch.hpp"
+
+namespace kan {
+
+// one thread per (sample, input): evaluate the pair and write its (rows + 1) entries of Phi
+__global__ __launch_bounds__(256) void dense_expand_kernel(SplineGeom g, const float *__restrict__ x,
+                                                           float *__restrict__ phi, int64_t B)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= B * g.n_in) return;
+    const int i = (int)(p % g.n_in);
+    const Pair pr = pair_eval<false>(x[p], g, i);
+    float *out = phi + p * (g.rows + 1);
+    for (int m = 0; m < g.rows; ++m) {
+        const int s = m - pr.cell;
+        float v = 0.0f;
+#pragma unroll
+        for (int q = 0; q < kMaxK; ++q) v = (s == q) ? pr.w[q] : v;
+        out[m] = v;
+    }
+    out[g.rows] = pr.base;
+}
+
+}  // namespace kan
+
+using namespace kan;
+
+namespace {
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+rocblas_handle g_handle = nullptr;
+}  // namespace
+
+extern "C" size_t kan_dense_baseline_workspace_bytes(const kan_layer_desc *d, int64_t B)
+{
+    if (!d || d->n_in <= 0 || d->n_out <= 0 || d->G <= 0 || d->k < 1 || d->k > 3 || B < 0) return 0;
+    const size_t kd = (size_t)d->n_in * (size_t)(d->G + d->k + 1);
+    return align_up(kd * (size_t)d->n_out * sizeof(float)) + align_up((size_t)B * kd * sizeof(float));
+}
+
+extern "C" int kan_dense_baseline_forward(const kan_layer_desc *d, int64_t B, const float *x, const float *coef,
+                                          const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
+                                          void *stream)
+{
+    if (!d || !x || !coef || !w_s || !y) return KAN_ERR_INVALID_ARG;
+    const size_t need = kan_dense_baseline_workspace_bytes(d, B);
+    if (need == 0 || !(d->grid_hi > d->grid_lo)) return KAN_ERR_INVALID_ARG;
+    if (d->base_act != KAN_BASE_NONE && !w_b) return KAN_ERR_INVALID_ARG;
+    if (B == 0) return KAN_OK;
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < need) return KAN_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    SplineGeom g;
+    g.n_in = d->n_in; g.n_out = d->n_out; g.rows = d->G + d->k; g.slab_rows = g.rows + 1; g.k = d->k;
+    g.lo = d->grid_lo; g.inv_h = (float)d->G / (d->grid_hi - d->grid_lo);
+    g.cell_base = nullptr; g.base_act = d->base_act;
+    const int64_t kd = (int64_t)g.n_in * g.slab_rows;
+    float *cf = (float *)ws;
+    float *phi = (float *)((char *)ws + align_up((size_t)kd * g.n_out * sizeof(float)));
+    if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    {
+        prof::Timed tm("dense_expand", st);
+        const int64_t pairs = B * g.n_in;
+        dense_expand_kernel<<<(unsigned)((pairs + 255) / 256), 256, 0, st>>>(g, x, phi, B);
+        if (hipGetLastError() != hipSuccess) return KAN_ERR_HIP;
+    }
+    if (!g_handle && rocblas_create_handle(&g_handle) != rocblas_status_success) return KAN_ERR_HIP;
+    if (rocblas_set_stream(g_handle, st) != rocblas_status_success) return KAN_ERR_HIP;
+    const float one = 1.0f, zero = 0.0f;
+    prof::Timed tm("dense_gemm", st);
+    // row-major y[B][n_out] = phi[B][kd] * cf[kd][n_out]  ==  column-major y^T = cf^T * phi^T
+    rocblas_status rs = rocblas_sgemm(g_handle, rocblas_operation_none, rocblas_operation_none, g.n_out, (int)B,
+                                      (int)kd, &one, cf, g.n_out, phi, (int)kd, &zero, y, g.n_out);
+    return rs == rocblas_status_success ? KAN_OK : KAN_ERR_HIP;
+}

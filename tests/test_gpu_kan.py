@@ -234,3 +234,15 @@ def test_config4_large_grid_sampled():
                               s.grid_lo, inv_h, want=("gcoef", "gw_s", "gw_b"))
     for name in ("gcoef", "gw_s", "gw_b"):
         assert_close(g[name][torch.from_numpy(ins).cuda()], ref[name], GRAD_TOL, name)
+
+
+def test_dense_gemm_baseline_matches_oracle():
+    """The comparison baseline (all G+k bases, one rocBLAS GEMM) computes the same forward pass."""
+    for B, n_in, n_out, G, k in [(300, 20, 96, 8, 3), (129, 7, 33, 5, 2)]:
+        w = workloads.random_kan_layer(900 + B, B, n_in, n_out, G, k, outside_frac=0.2)
+        s, p = w.layers[0], w.params[0]
+        inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+        x, coef, w_s, w_b = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"]))
+        y = binding.kan_dense_baseline_forward(s, x, coef, w_s, w_b)
+        torch.cuda.synchronize()
+        assert_close(y, oracle.kan_forward(w.x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h), FWD_TOL, "y")

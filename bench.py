@@ -32,7 +32,8 @@ MEASURED_TRAFFIC_BYTES_C3 = {
 
 KERNEL_ROLE = {  # kernel family -> which third of the fwd+bwd work it carries
     "forward_generic": "forward", "dx_generic": "dx", "dparam_generic": "dparam",
-    "forward_lds": "forward", "dx_lds": "dx", "dparam_sorted": "dparam",
+    "forward_lds": "forward", "dx_lds": "dx", "dparam_sorted": "dparam", "dparam_walk": "dparam",
+    "forward_narrow": "forward", "dx_narrow": "dx", "dparam_narrow": "dparam",
 }
 
 

@@ -48,7 +48,8 @@ size_t edge_bytes(const kan_layer_desc *d)
 
 // which kernels the backward pass uses and how its scratch is cut
 struct BackwardPlan {
-    bool sorted, narrow;
+    bool sorted, narrow, walk;
+    WalkPlan wp;
     ChunkPlan cp;
     size_t rec_bytes;       // one record array (0 for the generic path)
     int b_slices_per_chunk; // base-term partial slices each chunk writes
@@ -60,7 +61,15 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     BackwardPlan bp;
     bp.narrow = narrow_applicable(g) != 0;
     bp.sorted = !bp.narrow && backward_sorted_applicable(g) != 0;
-    if (bp.sorted) {
+    bp.wp = plan_walk(g, B);
+    bp.walk = prefer_walk(g, bp.wp, bp.sorted);
+    if (bp.walk) {
+        bp.sorted = bp.narrow = false;
+        bp.cp.n_chunks = bp.wp.n_chunks;
+        bp.cp.chunk_len = bp.wp.S;
+        bp.rec_bytes = align_up(walk_scratch_bytes(bp.wp, B, g.n_in));
+        bp.b_slices_per_chunk = 1;
+    } else if (bp.sorted) {
         bp.cp = plan_chunks_sorted(B, g.n_in, g.rows, g.n_out, dparam_sorted_waves(g.rows));
         bp.rec_bytes = align_up(pair_record_bytes(B, g.n_in));
         bp.b_slices_per_chunk = dparam_sorted_row_blocks(g.rows);
@@ -151,7 +160,10 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         float *part_c = (float *)at;
         float *part_b = (float *)((char *)part_c + (size_t)cp.n_chunks * folded_bytes(desc));
         // partial slabs are laid out back to back with the unpadded slab size
-        if (bp.sorted) {
+        if (bp.walk) {
+            if (launch_dparam_walk(g, bp.wp, x, gy, rec_w, part_c, want_b ? part_b : nullptr, B, st) != hipSuccess)
+                return KAN_ERR_HIP;
+        } else if (bp.sorted) {
             if (launch_pair_records(g, x, B, rec_w, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
             if (launch_dparam_sorted(g, rec_w, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
                                      st) != hipSuccess)

@@ -122,6 +122,29 @@ __device__ __forceinline__ Pair pair_eval(float x, const SplineGeom &g, int i)
     return p;
 }
 
+// Window form of a pair: a window of kMaxK consecutive rows that lies inside the table (first row
+// `row0` in [0, rows - kMaxK]) with the weights shifted to match, so that callers never index
+// outside the table.  Needs rows >= kMaxK.
+template <bool GRAD>
+__device__ __forceinline__ void window_of(const Pair &p, int rows, int &row0, float (&w)[kMaxK], float &base)
+{
+    const int hi = rows - kMaxK;
+    const int cc = p.cell < 0 ? 0 : (p.cell > hi ? hi : p.cell);
+    const int d = cc - p.cell;
+#pragma unroll
+    for (int s = 0; s < kMaxK; ++s) {
+        float v = 0.0f;
+#pragma unroll
+        for (int q = 0; q < kMaxK; ++q) {
+            const float src = GRAD ? p.dw[q] : p.w[q];
+            v = (s + d == q) ? src : v;
+        }
+        w[s] = v;
+    }
+    row0 = cc;
+    base = GRAD ? p.dbase : p.base;
+}
+
 // value of lane `src` (wave-uniform index) as a scalar
 __device__ __forceinline__ float lane_f(float v, int src)
 {

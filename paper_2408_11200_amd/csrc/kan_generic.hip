@@ -376,29 +376,77 @@ __global__ __launch_bounds__(256) void dparam_reduce_rows_kernel(float *__restri
     if (keep_sum) part_c[at] = (float)a;
 }
 
-// 2b: one thread per (input, output): gw_s from the summed acc, gw_b from the base slices.
+// 2a for n_out % 4 == 0: four consecutive outputs per thread, 16-byte accesses.
+__global__ __launch_bounds__(256) void dparam_reduce_rows4_kernel(float *__restrict__ part_c,
+                                                                  const float *__restrict__ w_s,
+                                                                  float *__restrict__ gcoef, int n_in, int rows,
+                                                                  int n_out, int n_chunks, int keep_sum)
+{
+    const int64_t slab = (int64_t)n_in * rows * n_out;
+    const int64_t at = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (at >= slab) return;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    int c = 0;
+    for (; c + 4 <= n_chunks; c += 4) {          // four loads in flight, summed in chunk order
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4 *>(part_c + (c + u) * slab + at);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { a0 += (double)v[u].x; a1 += (double)v[u].y; a2 += (double)v[u].z; a3 += (double)v[u].w; }
+    }
+    for (; c < n_chunks; ++c) {
+        const float4 v = *reinterpret_cast<const float4 *>(part_c + c * slab + at);
+        a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
+    }
+    const int j = (int)(at % n_out);
+    const int i = (int)(at / ((int64_t)rows * n_out));
+    if (gcoef) {
+        const float4 w = *reinterpret_cast<const float4 *>(w_s + (int64_t)i * n_out + j);
+        *reinterpret_cast<float4 *>(gcoef + at) = make_float4((float)((double)w.x * a0), (float)((double)w.y * a1),
+                                                              (float)((double)w.z * a2), (float)((double)w.w * a3));
+    }
+    if (keep_sum) *reinterpret_cast<float4 *>(part_c + at) = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
+}
+
+// 2b: gw_s from the summed acc, gw_b from the base slices.  grid (n_in, ceil(n_out / 64)), 256
+// threads: lane <-> output, the four waves split the rows (or slices) between them and their fp64
+// partial sums are added in wave order.
 __global__ __launch_bounds__(256) void dparam_reduce_edges_kernel(const float *__restrict__ acc_sum,
                                                                   const float *__restrict__ part_b,
                                                                   const float *__restrict__ coef,
                                                                   float *__restrict__ gw_s, float *__restrict__ gw_b,
                                                                   int n_in, int rows, int n_out, int n_slices_b)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (int64_t)n_in * n_out) return;
-    const int i = (int)(e / n_out), j = (int)(e % n_out);
+    __shared__ double part[2][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = blockIdx.x, j = blockIdx.y * 64 + lane;
+    const bool ok = j < n_out;
+    const int jc = ok ? j : 0;
+    double s = 0.0, a = 0.0;
     if (gw_s) {
-        double s = 0.0;
-        for (int m = 0; m < rows; ++m) {
-            const int64_t at = ((int64_t)i * rows + m) * n_out + j;
-            s += (double)coef[at] * (double)acc_sum[at];
+        const float *cp = coef + (int64_t)i * rows * n_out + jc, *ap = acc_sum + (int64_t)i * rows * n_out + jc;
+        int m = wave;
+        for (; m + 12 < rows; m += 16) {        // four rows of this wave in flight
+            float cv[4], av[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { cv[u] = cp[(int64_t)(m + 4 * u) * n_out]; av[u] = ap[(int64_t)(m + 4 * u) * n_out]; }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s += (double)cv[u] * (double)av[u];
         }
-        gw_s[e] = (float)s;
+        for (; m < rows; m += 4) s += (double)cp[(int64_t)m * n_out] * (double)ap[(int64_t)m * n_out];
     }
-    if (gw_b) {
-        double a = 0.0;
-        if (part_b)      // no base term: the gradient is identically zero
-            for (int c = 0; c < n_slices_b; ++c) a += (double)part_b[(int64_t)c * n_in * n_out + e];
-        gw_b[e] = (float)a;
+    if (gw_b && part_b) {
+        const float *bp = part_b + (int64_t)i * n_out + jc;
+        for (int c = wave; c < n_slices_b; c += 4) a += (double)bp[(int64_t)c * n_in * n_out];
+    }
+    part[0][wave][lane] = s;
+    part[1][wave][lane] = a;
+    __syncthreads();
+    if (wave == 0 && ok) {
+        const int64_t e = (int64_t)i * n_out + j;
+        if (gw_s) gw_s[e] = (float)(((part[0][0][lane] + part[0][1][lane]) + part[0][2][lane]) + part[0][3][lane]);
+        // no base term: the gradient is identically zero
+        if (gw_b) gw_b[e] = (float)(((part[1][0][lane] + part[1][1][lane]) + part[1][2][lane]) + part[1][3][lane]);
     }
 }
 
@@ -497,13 +545,23 @@ hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float 
                                 int n_chunks, int n_slices_b, hipStream_t st)
 {
     const int64_t slab = (int64_t)n_in * rows * n_out, edges = (int64_t)n_in * n_out;
-    prof::Timed tm("dparam_reduce", st);
-    if (gcoef || gw_s)
-        dparam_reduce_rows_kernel<<<(unsigned)((slab + 255) / 256), 256, 0, st>>>(part_c, w_s, gcoef, n_in, rows, n_out,
-                                                                                n_chunks, gw_s ? 1 : 0);
-    if (gw_s || gw_b)
-        dparam_reduce_edges_kernel<<<(unsigned)((edges + 255) / 256), 256, 0, st>>>(part_c, part_b, coef, gw_s, gw_b,
-                                                                                  n_in, rows, n_out, n_slices_b);
+    const bool vec4 = n_out % 4 == 0 && ((uintptr_t)part_c % 16) == 0 && (!gcoef || ((uintptr_t)gcoef % 16) == 0) &&
+                      ((uintptr_t)w_s % 16) == 0;
+    if (gcoef || gw_s) {
+        prof::Timed tm("dparam_reduce", st);
+        if (vec4)
+            dparam_reduce_rows4_kernel<<<(unsigned)((slab / 4 + 255) / 256), 256, 0, st>>>(part_c, w_s, gcoef, n_in, rows,
+                                                                                     n_out, n_chunks, gw_s ? 1 : 0);
+        else
+            dparam_reduce_rows_kernel<<<(unsigned)((slab + 255) / 256), 256, 0, st>>>(part_c, w_s, gcoef, n_in, rows,
+                                                                                    n_out, n_chunks, gw_s ? 1 : 0);
+    }
+    (void)edges;
+    if (gw_s || gw_b) {
+        prof::Timed te("dparam_reduce_edges", st);
+        dparam_reduce_edges_kernel<<<dim3((unsigned)n_in, (unsigned)((n_out + 63) / 64)), 256, 0, st>>>(
+            part_c, part_b, coef, gw_s, gw_b, n_in, rows, n_out, n_slices_b);
+    }
     return hipGetLastError();
 }
 

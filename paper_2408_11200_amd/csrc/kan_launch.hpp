@@ -75,6 +75,22 @@ hipError_t launch_pair_records(const SplineGeom &g, const float *x, int64_t B, P
 hipError_t launch_dparam_sorted(const SplineGeom &g, const PairRecord *rec, const float *gy, float *part_c,
                                 float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
 
+// Chunk-sorted walk (large grids, narrow layers).  plan_walk().ok == 0: shape not covered.
+struct WalkPlan {
+    int ok;
+    int S, sbits;        // samples per chunk (power of two) and its log2
+    int n_chunks;
+    int streams, T;      // streams per wave, outputs per lane
+    int n_jt;            // output tiles of (64 / streams) * T outputs
+    int row_bits;        // bits of the largest window row (sort key width)
+};
+WalkPlan plan_walk(const SplineGeom &g, int64_t B);
+size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in);
+// whether the walk should replace the tile-sorted / narrow / generic parameter-gradient kernel
+bool prefer_walk(const SplineGeom &g, const WalkPlan &p, bool tile_sorted_applicable);
+hipError_t launch_dparam_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy, void *scratch,
+                              float *part_c, float *part_b, int64_t B, hipStream_t st);
+
 // Chunking for the sorted kernels: whole tiles of 64 samples per chunk, enough chunks to give the
 // chip about two rounds of workgroups, chunks of at most 4096 samples (accuracy of the fp32 partial
 // sums), at most 64 chunks and at most 512 MiB of partial sums.

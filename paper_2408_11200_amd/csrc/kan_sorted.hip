@@ -16,27 +16,6 @@ namespace {
 
 constexpr int kTile = 64;          // samples per tile = lanes per wave
 
-// window form of a pair (see kan_lds.hip): first row in [0, rows - K], weights shifted to match
-template <bool GRAD>
-__device__ __forceinline__ void window_of(const Pair &p, int rows, int &row0, float (&w)[kMaxK], float &base)
-{
-    const int hi = rows - kMaxK;
-    const int cc = p.cell < 0 ? 0 : (p.cell > hi ? hi : p.cell);
-    const int d = cc - p.cell;
-#pragma unroll
-    for (int s = 0; s < kMaxK; ++s) {
-        float v = 0.0f;
-#pragma unroll
-        for (int q = 0; q < kMaxK; ++q) {
-            const float src = GRAD ? p.dw[q] : p.w[q];
-            v = (s + d == q) ? src : v;
-        }
-        w[s] = v;
-    }
-    row0 = cc;
-    base = GRAD ? p.dbase : p.base;
-}
-
 }  // namespace
 
 // ---- pre-pass: pair records ----------------------------------------------------------------------

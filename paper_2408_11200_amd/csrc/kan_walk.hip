@@ -1,0 +1,405 @@
+// Parameter-gradient kernels for large grids and narrow layers, built on pair records that are
+// sorted by window row over a whole chunk of the batch.
+//
+// With many coefficient rows per input (G + k in the hundreds, or a generated UKAN table) a tile of
+// 64 samples touches each row at most a few times, so any scheme that keeps "all rows of an input"
+// or "a block of rows" in registers spends its time on rows that receive nothing.  Here the samples
+// of one chunk (S = 256 .. 8192 samples) are sorted by the first row of their window, per input.  A
+// stream (one input, one tile of outputs, one chunk) then walks its list once: the window rows of
+// consecutive records never move backwards, so K accumulators per output slide along the rows; a
+// row is written out the moment the window has passed it and rows that no sample touched are
+// written as zeros on the way.  Work per stream is (records) x (K + 1) multiply-adds plus one
+// 16-byte store per row -- independent of the grid size (section "Algorithm": cost of the local
+// form does not grow with G).
+//
+//   1. transpose_kernel     x[B][n_in] -> xT[n_in][B], so that one input's samples are contiguous
+//   2. cell_sort_kernel     per (chunk, input): stable LSD radix sort of the S samples by window row
+//                           in LDS, then one PairRecord per sample in sorted order
+//   3. dparam_walk_kernel   the walk; partial sums per chunk, reduced by dparam_reduce (fp64,
+//                           fixed order), so results are bit-reproducible
+//
+// Lanes <-> outputs.  A wave holds 64 / LPS streams of LPS lanes each (LPS = 16, 32 or 64), so that
+// narrow layers still fill the wave.  Records are loaded 16 at a time, one per lane of each DPP row
+// of 16 lanes, and broadcast inside the row with row_newbcast; there is no scalar state, hence
+// streams in one wave may diverge freely.
+#include <type_traits>
+#include "kan_device.hpp"
+#include "kan_launch.hpp"
+
+namespace kan {
+
+namespace {
+
+constexpr int kSortThreads = 256;
+
+// ---- 1. transpose --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ x, float *__restrict__ xT,
+                                                        int64_t B, int n_in)
+{
+    __shared__ float tile[64][65];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t b0 = (int64_t)blockIdx.x * 64;
+    const int i0 = blockIdx.y * 64;
+    for (int r = ty; r < 64; r += 4)
+        tile[r][tx] = (b0 + r < B && i0 + tx < n_in) ? x[(b0 + r) * n_in + i0 + tx] : 0.0f;
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4)
+        if (i0 + r < n_in && b0 + tx < B) xT[(int64_t)(i0 + r) * B + b0 + tx] = tile[tx][r];
+}
+
+// ---- 2. sort + records ---------------------------------------------------------------------
+// grid (n_chunks, n_in), 256 threads.  key = window row << sbits | sample index in the chunk
+// (sbits = log2 S): keys are distinct, and sorting them by the row digits with a stable counting
+// sort keeps samples of equal row in batch order, which fixes the summation order downstream.
+// Each wave owns a contiguous quarter of the sequence; digit counts are taken per wave, the
+// (digit, wave) prefix gives every wave its first slot per digit, and the wave then places its
+// keys batch by batch (rank inside a batch from ballots), so nothing depends on timing.
+// Entries past the end of the batch get the largest row and end up behind every real record.
+__global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, const float *__restrict__ xT, int64_t B,
+                                                                 int S, int sbits, int row_bits,
+                                                                 PairRecord *__restrict__ rec)
+{
+    extern __shared__ unsigned lds_u[];
+    unsigned *src = lds_u, *dst = lds_u + S;
+    float *xs = reinterpret_cast<float *>(lds_u + 2 * S);
+    __shared__ unsigned slot[4][256];
+    __shared__ unsigned wave_tot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x, i = blockIdx.y;
+    const int64_t b0 = (int64_t)c * S;
+    const int n_c = (int)((B - b0) < S ? (B - b0) : S);
+
+    for (int e = tid; e < S; e += kSortThreads) {
+        const bool live = e < n_c;
+        const float xv = live ? xT[(int64_t)i * B + b0 + e] : 0.0f;
+        xs[e] = xv;
+        int row0 = g.rows - kMaxK;
+        if (live) {
+            const Pair p = pair_eval<false>(xv, g, i);
+            float w[kMaxK], base;
+            window_of<false>(p, g.rows, row0, w, base);
+        }
+        src[e] = ((unsigned)row0 << sbits) | (unsigned)e;
+    }
+    __syncthreads();
+
+    const int per_wave = S / 4;
+    const int n_pass = (row_bits + 7) / 8;
+    const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const int shift = sbits + 8 * pass;
+        const int nbits = row_bits - 8 * pass < 8 ? row_bits - 8 * pass : 8;
+        for (int d = tid; d < 4 * 256; d += kSortThreads) (&slot[0][0])[d] = 0u;
+        __syncthreads();
+        for (int e = wave * per_wave + lane; e < (wave + 1) * per_wave; e += 64)
+            atomicAdd(&slot[wave][(src[e] >> shift) & 255u], 1u);
+        __syncthreads();
+        {
+            const unsigned c0 = slot[0][tid], c1 = slot[1][tid], c2 = slot[2][tid], c3 = slot[3][tid];
+            const unsigned tot = c0 + c1 + c2 + c3;
+            unsigned inc = tot;
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned v = __shfl_up(inc, o, 64);
+                if (lane >= o) inc += v;
+            }
+            if (lane == 63) wave_tot[wave] = inc;
+            __syncthreads();
+            unsigned before = 0;
+            for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
+            const unsigned ex = before + inc - tot;
+            slot[0][tid] = ex; slot[1][tid] = ex + c0; slot[2][tid] = ex + c0 + c1; slot[3][tid] = ex + c0 + c1 + c2;
+        }
+        __syncthreads();
+        for (int e0 = wave * per_wave; e0 < (wave + 1) * per_wave; e0 += 64) {
+            const unsigned key = src[e0 + lane];
+            const int d = (int)((key >> shift) & 255u);
+            // lanes holding the same digit: intersect, bit by bit, the ballots of "my value of that bit"
+            unsigned long long same = ~0ull;
+            for (int bit = 0; bit < nbits; ++bit) {
+                const bool set = ((d >> bit) & 1) != 0;
+                const unsigned long long m = __ballot(set);
+                same &= set ? m : ~m;
+            }
+            const unsigned rank = (unsigned)__builtin_popcountll(same & below);
+            const unsigned first = slot[wave][d];
+            dst[first + rank] = key;
+            atomicAdd(&slot[wave][d], 1u);
+        }
+        __syncthreads();
+        unsigned *t = src; src = dst; dst = t;
+    }
+
+    PairRecord *out = rec + ((int64_t)c * g.n_in + i) * S;
+    for (int p = tid; p < S; p += kSortThreads) {
+        const int e = (int)(src[p] & (unsigned)(S - 1));
+        const bool live = e < n_c;
+        const Pair pr = pair_eval<false>(xs[e], g, i);
+        PairRecord r;
+        int row0;
+        window_of<false>(pr, g.rows, row0, r.w, r.base);
+        if (!live) {
+            row0 = g.rows - kMaxK;
+#pragma unroll
+            for (int s = 0; s < kMaxK; ++s) r.w[s] = 0.0f;
+            r.base = 0.0f;
+        }
+        r.rt = row0 | ((live ? e : 0) << 16);
+        out[p] = r;
+    }
+}
+
+// ---- 3. walk -------------------------------------------------------------------------------
+template <int N>
+__device__ __forceinline__ int row_bcast(int v)        // value of lane N of the caller's row of 16 lanes
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + N, 0xF, 0xF, true);
+}
+template <int N>
+__device__ __forceinline__ float row_bcast(float v)
+{
+    return __builtin_bit_cast(float, row_bcast<N>(__builtin_bit_cast(int, v)));
+}
+
+template <int N, int END, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N < END) {
+        f(std::integral_constant<int, N>{});
+        static_for<N + 1, END>(f);
+    }
+}
+
+template <int T>
+__device__ __forceinline__ void load_vec(const float *p, float (&v)[T])
+{
+    if constexpr (T == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        static_assert(T == 1, "one or four outputs per lane");
+        v[0] = *p;
+    }
+}
+template <int T>
+__device__ __forceinline__ void store_vec(float *p, const float (&v)[T])
+{
+    if constexpr (T == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    else p[0] = v[0];
+}
+
+// 4 waves per block, STREAMS streams per wave; stream number w = ((chunk * n_jt) + jt) * n_in + i,
+// so that the streams of a wave gather gy rows of the same chunk.  Per record: one gather of the
+// sample's gy row (T floats per lane), K + 1 broadcasts, (K + 1) * T multiply-adds.  Sums are kept
+// in two levels (the running sums are folded into a second set every 256 records) so that a long
+// run of samples in one cell does not lose accuracy to sequential fp32 accumulation.
+template <int STREAMS, int T>
+__global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const PairRecord *__restrict__ rec,
+                                                          const float *__restrict__ gy, float *__restrict__ part_c,
+                                                          float *__restrict__ part_b, int64_t B, int S, int n_chunks,
+                                                          int n_jt, int blocks_per_chunk, int xcd_groups)
+{
+    constexpr int LPS = 64 / STREAMS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane / LPS, q = lane % LPS, r16 = lane & 15;
+    // Workgroups go to the 8 XCDs round-robin.  The XCDs form m = min(8, n_chunks) groups (m a power of
+    // two); chunk c is handled by group c % m only, so that the gy rows a chunk's streams gather
+    // (every input re-reads them) stay in the L2 of the XCDs of one group.
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int grp = xcd % xcd_groups, n_sub = 8 / xcd_groups, sub_x = xcd / xcd_groups;
+    const int bpc_sub = (blocks_per_chunk + n_sub - 1) / n_sub;
+    const int c = grp + xcd_groups * (slot / bpc_sub);
+    const int blk = (slot % bpc_sub) * n_sub + sub_x;
+    const int ws = (blk * 4 + wave) * STREAMS + sub;
+    if (c >= n_chunks || blk >= blocks_per_chunk || ws >= n_jt * g.n_in) return;
+    const int i = ws % g.n_in;
+    const int jt = ws / g.n_in;
+    const int j = (jt * LPS + q) * T;
+    const bool jok = j < g.n_out;
+    const int jc = jok ? j : 0;
+    const int64_t b0 = (int64_t)c * S;
+    const int n_c = (int)((B - b0) < S ? (B - b0) : S);
+    const PairRecord *list = rec + ((int64_t)c * g.n_in + i) * S;
+    const float *gyp = gy + b0 * g.n_out + jc;
+    float *out = part_c + ((int64_t)c * g.n_in + i) * g.rows * g.n_out + jc;
+
+    float a[kMaxK][T], hi[kMaxK][T], ab[T], abh[T], zero[T];
+#pragma unroll
+    for (int r = 0; r < T; ++r) {
+        ab[r] = 0.0f; abh[r] = 0.0f; zero[r] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < kMaxK; ++s) { a[s][r] = 0.0f; hi[s][r] = 0.0f; }
+    }
+
+    int cur = list[0].rt & 0xffff;           // first row of the window the accumulators stand on
+    if (jok)
+        for (int m = 0; m < cur; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
+
+    const int nb = (n_c + 15) / 16;
+    PairRecord mine = list[r16];
+    for (int bi = 0; bi < nb; ++bi) {
+        const PairRecord upcoming = list[(bi + 1 < nb ? bi + 1 : bi) * 16 + r16];
+        const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
+        auto half = [&](auto h) {
+            constexpr int H = decltype(h)::value;
+            float gr[8][T];
+            static_for<0, 8>([&](auto n) {
+                constexpr int N = decltype(n)::value;
+                const int t = row_bcast<H * 8 + N>(tv);
+                load_vec<T>(gyp + (int64_t)t * g.n_out, gr[N]);
+            });
+            static_for<0, 8>([&](auto n) {
+                constexpr int N = decltype(n)::value;
+                const int row0 = row_bcast<H * 8 + N>(rowv);
+                while (cur < row0) {            // the window moves on: its first row is complete
+                    if (jok) {
+                        float o[T];
+#pragma unroll
+                        for (int r = 0; r < T; ++r) o[r] = a[0][r] + hi[0][r];
+                        store_vec<T>(out + (int64_t)cur * g.n_out, o);
+                    }
+#pragma unroll
+                    for (int r = 0; r < T; ++r) {
+#pragma unroll
+                        for (int s = 0; s + 1 < kMaxK; ++s) { a[s][r] = a[s + 1][r]; hi[s][r] = hi[s + 1][r]; }
+                        a[kMaxK - 1][r] = 0.0f; hi[kMaxK - 1][r] = 0.0f;
+                    }
+                    ++cur;
+                }
+                const float w0 = row_bcast<H * 8 + N>(mine.w[0]), w1 = row_bcast<H * 8 + N>(mine.w[1]);
+                const float w2 = row_bcast<H * 8 + N>(mine.w[2]), w3 = row_bcast<H * 8 + N>(mine.w[3]);
+                const float bs = row_bcast<H * 8 + N>(mine.base);
+#pragma unroll
+                for (int r = 0; r < T; ++r) {
+                    a[0][r] = fmaf(w0, gr[N][r], a[0][r]);
+                    a[1][r] = fmaf(w1, gr[N][r], a[1][r]);
+                    a[2][r] = fmaf(w2, gr[N][r], a[2][r]);
+                    a[3][r] = fmaf(w3, gr[N][r], a[3][r]);
+                    ab[r] = fmaf(bs, gr[N][r], ab[r]);
+                }
+            });
+        };
+        half(std::integral_constant<int, 0>{});
+        half(std::integral_constant<int, 1>{});
+        if ((bi & 15) == 15) {
+#pragma unroll
+            for (int r = 0; r < T; ++r) {
+#pragma unroll
+                for (int s = 0; s < kMaxK; ++s) { hi[s][r] += a[s][r]; a[s][r] = 0.0f; }
+                abh[r] += ab[r]; ab[r] = 0.0f;
+            }
+        }
+        mine = upcoming;
+    }
+
+    if (!jok) return;
+#pragma unroll
+    for (int s = 0; s < kMaxK; ++s) {
+        float o[T];
+#pragma unroll
+        for (int r = 0; r < T; ++r) o[r] = a[s][r] + hi[s][r];
+        store_vec<T>(out + (int64_t)(cur + s) * g.n_out, o);
+    }
+    for (int m = cur + kMaxK; m < g.rows; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
+    if (part_b) {
+        float o[T];
+#pragma unroll
+        for (int r = 0; r < T; ++r) o[r] = ab[r] + abh[r];
+        store_vec<T>(part_b + ((int64_t)c * g.n_in + i) * g.n_out + jc, o);
+    }
+}
+
+int log2_exact(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
+
+}  // namespace
+
+// ---- planning and launch ---------------------------------------------------------------------
+
+WalkPlan plan_walk(const SplineGeom &g, int64_t B)
+{
+    WalkPlan p = {};
+    if (g.rows < kMaxK || g.rows > 0xffff || B < 1) return p;
+    if (g.n_out % 4 == 0) {
+        p.T = 4;
+        p.streams = g.n_out > 128 ? 1 : (g.n_out > 64 ? 2 : 4);
+    } else if (g.n_out <= 16) {
+        p.T = 1;
+        p.streams = 4;
+    } else {
+        return p;
+    }
+    const int tile = (64 / p.streams) * p.T;
+    p.n_jt = (g.n_out + tile - 1) / tile;
+    // chunk length: a power of two between 256 and 8192 samples, the smallest of
+    //   - what keeps the gy rows of one chunk inside an XCD's L2 (about 2 MiB of it),
+    //   - what gives the chip about 2048 waves,
+    //   - an eighth of the batch (one chunk per XCD at least),
+    // then raised until the partial sums fit 2 GiB.
+    auto pow2_floor = [](int64_t v) { int64_t q = 256; while (q * 2 <= v && q < 8192) q *= 2; return (int)q; };
+    int S = pow2_floor((2ll << 20) / ((int64_t)g.n_out * 4));
+    const int s_par = pow2_floor(B * p.n_jt * g.n_in / ((int64_t)p.streams * 2048));
+    const int s_b8 = pow2_floor(B / 8);
+    S = S < s_par ? S : s_par;
+    S = S < s_b8 ? S : s_b8;
+    const int64_t slab = (int64_t)g.n_in * g.rows * g.n_out * (int64_t)sizeof(float);
+    while (S < 8192 && ((B + S - 1) / S) * slab > (2ll << 30)) S *= 2;
+    p.S = S;
+    p.sbits = log2_exact(S);
+    p.n_chunks = (int)((B + S - 1) / S);
+    int bits = 0;
+    while ((1 << bits) < g.rows - kMaxK + 1) ++bits;
+    p.row_bits = bits < 1 ? 1 : bits;
+    p.ok = (int64_t)p.n_chunks * slab <= (4ll << 30) ? 1 : 0;
+    return p;
+}
+
+bool prefer_walk(const SplineGeom &g, const WalkPlan &p, bool tile_sorted_applicable)
+{
+    (void)g; (void)tile_sorted_applicable;
+    return p.ok != 0;       // measured faster than the tile-sorted and narrow kernels on every shape it covers
+}
+
+size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
+{
+    const size_t xt = ((size_t)B * n_in * sizeof(float) + 255) / 256 * 256;
+    return xt + (size_t)p.n_chunks * n_in * p.S * sizeof(PairRecord);
+}
+
+hipError_t launch_dparam_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy, void *scratch,
+                              float *part_c, float *part_b, int64_t B, hipStream_t st)
+{
+    float *xT = (float *)scratch;
+    PairRecord *rec = (PairRecord *)((char *)scratch + ((size_t)B * g.n_in * sizeof(float) + 255) / 256 * 256);
+    {
+        dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
+        prof::Timed tm("walk_transpose", st);
+        transpose_kernel<<<grid, 256, 0, st>>>(x, xT, B, g.n_in);
+    }
+    {
+        const size_t lds = (size_t)p.S * 12;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(cell_sort_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        dim3 grid((unsigned)p.n_chunks, (unsigned)g.n_in);
+        prof::Timed tm("walk_sort", st);
+        cell_sort_kernel<<<grid, kSortThreads, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec);
+    }
+    const int bpc = (p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
+    int m = 1;
+    while (m * 2 <= 8 && m * 2 <= p.n_chunks) m *= 2;
+    const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
+    const unsigned blocks = (unsigned)(8 * bpc_sub * ((p.n_chunks + m - 1) / m));
+    prof::Timed tm("dparam_walk", st);
+    if (p.T == 4 && p.streams == 1)
+        dparam_walk_kernel<1, 4><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
+    else if (p.T == 4 && p.streams == 2)
+        dparam_walk_kernel<2, 4><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
+    else if (p.T == 4 && p.streams == 4)
+        dparam_walk_kernel<4, 4><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
+    else if (p.T == 1 && p.streams == 4)
+        dparam_walk_kernel<4, 1><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace kan

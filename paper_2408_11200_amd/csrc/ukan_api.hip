@@ -23,6 +23,40 @@ int check_desc(const ukan_layer_desc *d)
     return KAN_OK;
 }
 
+// the record-driven kernel needs n_out % 4 == 0 and n_out >= 64; narrow layers have their own
+bool use_sorted(const ukan_layer_desc *d) { return d->n_out % 4 == 0 && d->n_out >= 64; }
+
+// the walk is planned for the largest table the workspace allows, so that the chunking (and with it
+// the workspace layout) does not depend on the data
+WalkPlan walk_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
+{
+    SplineGeom g = {};
+    g.n_in = d->n_in; g.n_out = d->n_out; g.rows = max_groups * (d->k + 1); g.slab_rows = g.rows; g.k = d->k;
+    WalkPlan wp = plan_walk(g, B);
+    if (!prefer_walk(g, wp, use_sorted(d))) wp.ok = 0;
+    return wp;
+}
+
+// scratch of the record pre-pass, sized for whichever kernel the plan picks
+size_t record_bytes_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
+{
+    const WalkPlan wp = walk_for(d, B, max_groups);
+    return wp.ok ? walk_scratch_bytes(wp, B, d->n_in) : pair_record_bytes(B, d->n_in);
+}
+
+ChunkPlan chunks_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
+{
+    const int rows = max_groups * (d->k + 1);
+    const WalkPlan wp = walk_for(d, B, max_groups);
+    if (wp.ok) {
+        ChunkPlan cp;
+        cp.n_chunks = wp.n_chunks; cp.chunk_len = wp.S;
+        return cp;
+    }
+    if (use_sorted(d)) return plan_chunks_sorted(B, d->n_in, rows, d->n_out, dparam_sorted_waves(rows));
+    return plan_chunks(B, d->n_in, rows, d->n_out);
+}
+
 // Offsets (bytes) of every scratch region for `n_g` generator rows per input.
 struct Layout {
     size_t cmin, cmax, g_first, n_groups, cell_base, summary;
@@ -33,7 +67,7 @@ struct Layout {
 
 int split_slices(int64_t rows) { int64_t s = (rows + 511) / 512; return (int)(s < 1 ? 1 : (s > 64 ? 64 : s)); }
 
-Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunks, int pass)
+Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunks, size_t rec_bytes, int pass)
 {
     const size_t K = (size_t)d->k + 1, n_in = (size_t)d->n_in, n_out = (size_t)d->n_out;
     const size_t rows = n_in * (size_t)n_g, n_o = K * n_out, dz = (size_t)d->d_feat + d->d_pe, dh = (size_t)d->d_hidden;
@@ -50,7 +84,7 @@ Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunk
         L.z = take(rows * dz * 4);
         L.pre = take(rows * dh * 4);
         L.raw = take(table);
-        L.rec = take(pair_record_bytes(B, d->n_in));
+        L.rec = take(rec_bytes);
         L.part_c = take((size_t)n_chunks * table);
         L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);   // >= the slice count of the other kernels
         L.gout = take(table);
@@ -63,16 +97,6 @@ Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunk
     }
     L.total = at;
     return L;
-}
-
-// the record-driven kernel needs n_out % 4 == 0 and n_out >= 64; narrow layers have their own
-bool use_sorted(const ukan_layer_desc *d) { return d->n_out % 4 == 0 && d->n_out >= 64; }
-
-ChunkPlan chunks_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
-{
-    const int rows = max_groups * (d->k + 1);
-    if (use_sorted(d)) return plan_chunks_sorted(B, d->n_in, rows, d->n_out, dparam_sorted_waves(rows));
-    return plan_chunks(B, d->n_in, rows, d->n_out);
 }
 
 struct Prepared {
@@ -89,7 +113,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     const int K = d->k + 1;
     const float inv_h = 1.0f / d->h;
     out->cp = chunks_for(d, B, max_groups);
-    Layout L0 = make_layout(d, B, max_groups, out->cp.n_chunks, pass);     // meta offsets do not depend on n_g
+    Layout L0 = make_layout(d, B, max_groups, out->cp.n_chunks, record_bytes_for(d, B, max_groups), pass);     // meta offsets do not depend on n_g
     int32_t *cmin = (int32_t *)(ws + L0.cmin), *cmax = (int32_t *)(ws + L0.cmax);
     int32_t *g_first = (int32_t *)(ws + L0.g_first), *n_groups = (int32_t *)(ws + L0.n_groups);
     int32_t *cell_base = (int32_t *)(ws + L0.cell_base), *summary = (int32_t *)(ws + L0.summary);
@@ -100,7 +124,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     if (hipStreamSynchronize(st) != hipSuccess) return KAN_ERR_HIP;
     if (span < 2 || span > max_groups) return KAN_ERR_RANGE;
     out->n_g = span;
-    out->L = make_layout(d, B, span, out->cp.n_chunks, pass);
+    out->L = make_layout(d, B, span, out->cp.n_chunks, record_bytes_for(d, B, max_groups), pass);
     const Layout &L = out->L;
     const int64_t rows = (int64_t)d->n_in * span;
     const int64_t n_o = (int64_t)K * d->n_out;
@@ -151,7 +175,7 @@ extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *desc, int64_t B, i
     if (check_desc(desc) != KAN_OK || B < 0 || max_groups < 2) return 0;
     if (pass != KAN_PASS_FORWARD && pass != KAN_PASS_BACKWARD) return 0;
     ChunkPlan cp = chunks_for(desc, B, max_groups);
-    return make_layout(desc, B, max_groups, cp.n_chunks, pass).total;
+    return make_layout(desc, B, max_groups, cp.n_chunks, record_bytes_for(desc, B, max_groups), pass).total;
 }
 
 extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
@@ -202,8 +226,13 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
     float *gout = (float *)(w + L.gout);
     const bool sorted = !narrow && use_sorted(desc) && backward_sorted_applicable(pr.g);
+    const WalkPlan wp = walk_for(desc, B, max_groups);
     int b_slices;
-    if (sorted) {
+    if (wp.ok) {
+        if (launch_dparam_walk(pr.g, wp, x, gy, w + L.rec, part_c, want_b ? part_b : nullptr, B, st) != hipSuccess)
+            return KAN_ERR_HIP;
+        b_slices = pr.cp.n_chunks;
+    } else if (sorted) {
         PairRecord *rec = (PairRecord *)(w + L.rec);
         if (launch_pair_records(pr.g, x, B, rec, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
         if (launch_dparam_sorted(pr.g, rec, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,

@@ -46,12 +46,12 @@ size_t edge_bytes(const kan_layer_desc *d)
     return align_up((size_t)d->n_in * (size_t)d->n_out * sizeof(float));
 }
 
-// which kernels the backward pass uses and how its scratch is cut
+// which kernel takes the parameter gradients and how its scratch is cut
 struct BackwardPlan {
-    bool sorted, narrow, walk;
+    bool walk;
     WalkPlan wp;
     ChunkPlan cp;
-    size_t rec_bytes;       // one record array (0 for the generic path)
+    size_t rec_bytes;       // transposed x + sorted records of the walk (0 for the generic kernel)
     int b_slices_per_chunk; // base-term partial slices each chunk writes
 };
 
@@ -59,24 +59,17 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
 {
     SplineGeom g = geom_of(d);
     BackwardPlan bp;
-    bp.narrow = narrow_applicable(g) != 0;
-    bp.sorted = !bp.narrow && backward_sorted_applicable(g) != 0;
     bp.wp = plan_walk(g, B);
-    bp.walk = prefer_walk(g, bp.wp, bp.sorted);
+    bp.walk = bp.wp.ok != 0;
     if (bp.walk) {
-        bp.sorted = bp.narrow = false;
         bp.cp.n_chunks = bp.wp.n_chunks;
         bp.cp.chunk_len = bp.wp.S;
         bp.rec_bytes = align_up(walk_scratch_bytes(bp.wp, B, g.n_in));
         bp.b_slices_per_chunk = 1;
-    } else if (bp.sorted) {
-        bp.cp = plan_chunks_sorted(B, g.n_in, g.rows, g.n_out, dparam_sorted_waves(g.rows));
-        bp.rec_bytes = align_up(pair_record_bytes(B, g.n_in));
-        bp.b_slices_per_chunk = dparam_sorted_row_blocks(g.rows);
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
         bp.rec_bytes = 0;
-        bp.b_slices_per_chunk = bp.narrow ? dparam_narrow_row_blocks(g.rows) : dparam_generic_row_blocks(g.rows);
+        bp.b_slices_per_chunk = dparam_generic_row_blocks(g.rows);
     }
     return bp;
 }
@@ -155,26 +148,16 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         const BackwardPlan bp = backward_plan(desc, B);
         const ChunkPlan cp = bp.cp;
         char *at = (char *)ws + folded_bytes(desc);
-        PairRecord *rec_w = (PairRecord *)at;
+        void *walk_scratch = at;
         at += bp.rec_bytes;
         float *part_c = (float *)at;
         float *part_b = (float *)((char *)part_c + (size_t)cp.n_chunks * folded_bytes(desc));
         // partial slabs are laid out back to back with the unpadded slab size
-        if (bp.walk) {
-            if (launch_dparam_walk(g, bp.wp, x, gy, rec_w, part_c, want_b ? part_b : nullptr, B, st) != hipSuccess)
-                return KAN_ERR_HIP;
-        } else if (bp.sorted) {
-            if (launch_pair_records(g, x, B, rec_w, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
-            if (launch_dparam_sorted(g, rec_w, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
-                                     st) != hipSuccess)
-                return KAN_ERR_HIP;
-        } else if (bp.narrow) {
-            if (launch_dparam_narrow(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
-                                     st) != hipSuccess)
-                return KAN_ERR_HIP;
-        } else if (launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks, cp.chunk_len,
-                                         st) != hipSuccess)
-            return KAN_ERR_HIP;
+        hipError_t e = bp.walk ? launch_dparam_walk(g, bp.wp, x, gy, walk_scratch, part_c, want_b ? part_b : nullptr,
+                                                    B, st)
+                               : launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks,
+                                                       cp.chunk_len, st);
+        if (e != hipSuccess) return KAN_ERR_HIP;
         if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
                                  g.n_out, cp.n_chunks, cp.n_chunks * bp.b_slices_per_chunk, st) != hipSuccess)
             return KAN_ERR_HIP;

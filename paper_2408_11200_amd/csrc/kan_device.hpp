@@ -78,8 +78,12 @@ __device__ __forceinline__ Pair pair_eval(float x, const SplineGeom &g, int i)
     long long rel = (long long)idx - (g.cell_base ? (long long)g.cell_base[i] : 0ll);
     rel = rel < -kMaxK ? -kMaxK : (rel > g.rows ? g.rows : rel);
     p.cell = (int)rel;
-    // local coordinate: exact product minus the integer, one rounding
-    float u = fmaf(d, g.inv_h, -floorf(t));
+    // local coordinate: exact product minus the integer, one rounding; the rounding error of the
+    // subtraction x - lo (recovered exactly by the two-sum below) is added back, because the
+    // x-derivative multiplies it by inv_h twice and fine grids would otherwise lose digits
+    const float bb = __fsub_rn(d, x);                                          // ~ -lo
+    const float d_err = __fadd_rn(__fsub_rn(x, __fsub_rn(d, bb)), __fsub_rn(-g.lo, bb));
+    float u = fmaf(d_err, g.inv_h, fmaf(d, g.inv_h, -floorf(t)));
 
     // Cox-de Boor on one cell of a uniform grid:
     //   N^d_s = ((u + d - s) N^{d-1}_{s-1} + (s + 1 - u) N^{d-1}_s) / d

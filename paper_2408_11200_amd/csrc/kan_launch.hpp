@@ -41,13 +41,10 @@ hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float 
 
 // narrow layers (n_out <= 16)
 int narrow_applicable(const SplineGeom &g);
-int dparam_narrow_row_blocks(int rows);
 hipError_t launch_forward_narrow(const SplineGeom &g, const float *x, const float *cf, const float *w_b, float *y,
                                  int64_t B, hipStream_t st);
 hipError_t launch_dx_narrow(const SplineGeom &g, const float *x, const float *cf, const float *w_b, const float *gy,
                             float *gx, int64_t B, hipStream_t st);
-hipError_t launch_dparam_narrow(const SplineGeom &g, const float *x, const float *gy, float *part_c, float *part_b,
-                                int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
 
 // LDS-staged kernels (small grids); *_plan returns 0 when the shape does not qualify
 int forward_lds_plan(const SplineGeom &g);
@@ -58,22 +55,13 @@ int dx_lds_plan(const SplineGeom &g);
 hipError_t launch_dx_lds(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx, int64_t B,
                          hipStream_t st);
 
-// Record-driven kernels (small grids).  One record per (sample, input) pair, stored
-// [tile of 64 samples][input][rank by window row]: first window row, sample index in the tile, the K window weights (or their x-derivatives) and the base value
-// (or derivative).
+// One record per (sample, input) pair: first row of the K-wide window (clamped into the table),
+// the sample's index inside its chunk, the K window weights and the base value.
 struct PairRecord {
-    int rt;             // first window row | sample index in the tile << 16
+    int rt;             // first window row | sample index in the chunk << 16
     float w[kMaxK];
     float base;
 };
-int backward_sorted_applicable(const SplineGeom &g);
-int dparam_sorted_waves(int rows);
-int dparam_sorted_row_blocks(int rows);
-size_t pair_record_bytes(int64_t B, int n_in);
-hipError_t launch_pair_records(const SplineGeom &g, const float *x, int64_t B, PairRecord *rec_w, PairRecord *rec_d,
-                            hipStream_t st);
-hipError_t launch_dparam_sorted(const SplineGeom &g, const PairRecord *rec, const float *gy, float *part_c,
-                                float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
 
 // Chunk-sorted walk (large grids, narrow layers).  plan_walk().ok == 0: shape not covered.
 struct WalkPlan {
@@ -86,16 +74,8 @@ struct WalkPlan {
 };
 WalkPlan plan_walk(const SplineGeom &g, int64_t B);
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in);
-// whether the walk should replace the tile-sorted / narrow / generic parameter-gradient kernel
-bool prefer_walk(const SplineGeom &g, const WalkPlan &p, bool tile_sorted_applicable);
 hipError_t launch_dparam_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy, void *scratch,
                               float *part_c, float *part_b, int64_t B, hipStream_t st);
-
-// Chunking for the sorted kernels: whole tiles of 64 samples per chunk, enough chunks to give the
-// chip about two rounds of workgroups, chunks of at most 4096 samples (accuracy of the fp32 partial
-// sums), at most 64 chunks and at most 512 MiB of partial sums.
-struct ChunkPlan;
-ChunkPlan plan_chunks_sorted(int64_t B, int n_in, int rows, int n_out, int waves);
 
 // How the batch is cut into chunks for the parameter-gradient reduction: chunks of about 1024
 // samples, at most 64 of them, and no more than fit a 512 MiB budget of partial sums.
@@ -112,28 +92,6 @@ inline ChunkPlan plan_chunks(int64_t B, int n_in, int rows, int n_out)
     p.chunk_len = (B + n - 1) / n;
     if (p.chunk_len < 1) p.chunk_len = 1;
     p.n_chunks = (int)((B + p.chunk_len - 1) / p.chunk_len);
-    if (p.n_chunks < 1) p.n_chunks = 1;
-    return p;
-}
-
-inline ChunkPlan plan_chunks_sorted(int64_t B, int n_in, int rows, int n_out, int waves)
-{
-    const int64_t tiles = (B + 63) / 64;
-    const int64_t items = (int64_t)n_in * dparam_sorted_row_blocks(rows);
-    const int64_t wg_per_chunk = ((items + waves - 1) / waves) * ((n_out + 255) / 256);
-    int64_t n = (512 + wg_per_chunk - 1) / wg_per_chunk;
-    const int64_t by_len = (B + 4095) / 4096;
-    if (n < by_len) n = by_len;
-    const int64_t slab = (int64_t)n_in * rows * n_out * (int64_t)sizeof(float);
-    const int64_t by_budget = (512ll << 20) / (slab > 0 ? slab : 1);
-    if (n > by_budget) n = by_budget;
-    if (n > 64) n = 64;
-    if (n > tiles) n = tiles;
-    if (n < 1) n = 1;
-    ChunkPlan p;
-    const int64_t tiles_per = (tiles + n - 1) / n;
-    p.chunk_len = tiles_per * 64;
-    p.n_chunks = (int)((tiles + tiles_per - 1) / tiles_per);
     if (p.n_chunks < 1) p.n_chunks = 1;
     return p;
 }

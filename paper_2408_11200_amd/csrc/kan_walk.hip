@@ -352,12 +352,6 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
     return p;
 }
 
-bool prefer_walk(const SplineGeom &g, const WalkPlan &p, bool tile_sorted_applicable)
-{
-    (void)g; (void)tile_sorted_applicable;
-    return p.ok != 0;       // measured faster than the tile-sorted and narrow kernels on every shape it covers
-}
-
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
 {
     const size_t xt = ((size_t)B * n_in * sizeof(float) + 255) / 256 * 256;

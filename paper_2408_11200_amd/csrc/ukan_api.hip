@@ -23,38 +23,31 @@ int check_desc(const ukan_layer_desc *d)
     return KAN_OK;
 }
 
-// the record-driven kernel needs n_out % 4 == 0 and n_out >= 64; narrow layers have their own
-bool use_sorted(const ukan_layer_desc *d) { return d->n_out % 4 == 0 && d->n_out >= 64; }
-
 // the walk is planned for the largest table the workspace allows, so that the chunking (and with it
 // the workspace layout) does not depend on the data
 WalkPlan walk_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
     SplineGeom g = {};
     g.n_in = d->n_in; g.n_out = d->n_out; g.rows = max_groups * (d->k + 1); g.slab_rows = g.rows; g.k = d->k;
-    WalkPlan wp = plan_walk(g, B);
-    if (!prefer_walk(g, wp, use_sorted(d))) wp.ok = 0;
-    return wp;
+    return plan_walk(g, B);
 }
 
-// scratch of the record pre-pass, sized for whichever kernel the plan picks
+// scratch of the walk's pre-pass (transposed x + sorted records)
 size_t record_bytes_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
     const WalkPlan wp = walk_for(d, B, max_groups);
-    return wp.ok ? walk_scratch_bytes(wp, B, d->n_in) : pair_record_bytes(B, d->n_in);
+    return wp.ok ? walk_scratch_bytes(wp, B, d->n_in) : 0;
 }
 
 ChunkPlan chunks_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
-    const int rows = max_groups * (d->k + 1);
     const WalkPlan wp = walk_for(d, B, max_groups);
     if (wp.ok) {
         ChunkPlan cp;
         cp.n_chunks = wp.n_chunks; cp.chunk_len = wp.S;
         return cp;
     }
-    if (use_sorted(d)) return plan_chunks_sorted(B, d->n_in, rows, d->n_out, dparam_sorted_waves(rows));
-    return plan_chunks(B, d->n_in, rows, d->n_out);
+    return plan_chunks(B, d->n_in, max_groups * (d->k + 1), d->n_out);
 }
 
 // Offsets (bytes) of every scratch region for `n_g` generator rows per input.
@@ -225,28 +218,17 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     // table gradient: partial sums per batch chunk, then  gout = scale * sum,  gscale = sum_m raw * sum
     float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
     float *gout = (float *)(w + L.gout);
-    const bool sorted = !narrow && use_sorted(desc) && backward_sorted_applicable(pr.g);
     const WalkPlan wp = walk_for(desc, B, max_groups);
     int b_slices;
     if (wp.ok) {
         if (launch_dparam_walk(pr.g, wp, x, gy, w + L.rec, part_c, want_b ? part_b : nullptr, B, st) != hipSuccess)
             return KAN_ERR_HIP;
         b_slices = pr.cp.n_chunks;
-    } else if (sorted) {
-        PairRecord *rec = (PairRecord *)(w + L.rec);
-        if (launch_pair_records(pr.g, x, B, rec, nullptr, st) != hipSuccess) return KAN_ERR_HIP;
-        if (launch_dparam_sorted(pr.g, rec, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,
-                                 pr.cp.chunk_len, st) != hipSuccess)
-            return KAN_ERR_HIP;
-        b_slices = pr.cp.n_chunks * dparam_sorted_row_blocks(pr.g.rows);
     } else {
-        hipError_t e = narrow ? launch_dparam_narrow(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B,
-                                                     pr.cp.n_chunks, pr.cp.chunk_len, st)
-                              : launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B,
-                                                      pr.cp.n_chunks, pr.cp.chunk_len, st);
-        if (e != hipSuccess) return KAN_ERR_HIP;
-        b_slices = pr.cp.n_chunks * (narrow ? dparam_narrow_row_blocks(pr.g.rows)
-                                            : dparam_generic_row_blocks(pr.g.rows));
+        if (launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,
+                                  pr.cp.chunk_len, st) != hipSuccess)
+            return KAN_ERR_HIP;
+        b_slices = pr.cp.n_chunks * dparam_generic_row_blocks(pr.g.rows);
     }
     if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
                              cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,

@@ -67,6 +67,10 @@ SWEEP = [
     (96, 33, 512, 20, 3, 0.05),
     (200, 8, 256, 64, 1, 0.2),
     (65, 4, 7, 200, 3, 0.2),           # large grid, odd n_out
+    (700, 5, 32, 300, 3, 0.1),         # three ragged chunks, two sort digits, four streams per wave
+    (2100, 3, 132, 40, 2, 0.2),        # one stream per wave with a ragged output tile
+    (900, 6, 96, 7, 3, 0.3),           # two streams per wave
+    (300, 9, 12, 30, 3, 0.1),          # narrow layer, one output per lane
 ]
 
 
@@ -74,6 +78,21 @@ SWEEP = [
 def test_layer_parity_sweep(B, n_in, n_out, G, k, outside):
     w = workloads.random_kan_layer(100 + B + n_in + n_out, B, n_in, n_out, G, k, outside_frac=outside)
     run_layer_parity(w)
+
+
+def test_long_run_in_one_cell():
+    """Every sample of an input in the same cell: the longest possible run for the sliding-window sums."""
+    s = workloads.KanLayerSpec(2, 64, 6, 3, -1.0, 1.0)
+    rng = np.random.default_rng(11)
+    p = workloads.kan_params(rng, s, 0.1, w_s_std=1.0, w_b_std=1.0)
+    B = 6000
+    x = np.float32(np.stack([0.05 + 0.2 * rng.random(B), np.full(B, -0.4)], axis=1))
+    gy = np.float32(rng.standard_normal((B, 64)))
+    inv_h = oracle.inv_h_of(-1.0, 1.0, 6)
+    g = binding.kan_backward(s, dev(x), dev(p["coef"]), dev(p["w_s"]), dev(p["w_b"]), dev(gy))
+    ref = oracle.kan_backward(x, p["coef"], p["w_s"], p["w_b"], gy, 6, 3, -1.0, inv_h)
+    for name in ref:
+        assert_close(g[name], ref[name], GRAD_TOL, name)
 
 
 def test_no_base_term():

@@ -136,16 +136,23 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     hipStream_t st = (hipStream_t)stream;
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
+    const BackwardPlan bp = backward_plan(desc, B);
+    const bool want_params = gcoef || gw_s || gw_b;
+    // The chunk-sorted walk takes dL/dx together with the parameter gradients (one pass over gy),
+    // except for small-grid layers wider than one output tile, where the LDS-staged dL/dx kernel with
+    // its eight outputs per lane is the faster of the two.
+    const bool fused_dx = gx && bp.walk && !(bp.wp.n_jt > 1 && dx_lds_plan(g));
     if (gx) {
         if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
-        hipError_t e = narrow_applicable(g) ? launch_dx_narrow(g, x, cf, w_b, gy, gx, B, st)
-                       : dx_lds_plan(g)     ? launch_dx_lds(g, x, cf, gy, gx, B, st)
-                                            : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
-        if (e != hipSuccess) return KAN_ERR_HIP;
+        if (!fused_dx) {
+            hipError_t e = narrow_applicable(g) ? launch_dx_narrow(g, x, cf, w_b, gy, gx, B, st)
+                           : dx_lds_plan(g)     ? launch_dx_lds(g, x, cf, gy, gx, B, st)
+                                                : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
+            if (e != hipSuccess) return KAN_ERR_HIP;
+        }
     }
     const bool want_b = gw_b && desc->base_act != KAN_BASE_NONE;
-    if (gcoef || gw_s || gw_b) {
-        const BackwardPlan bp = backward_plan(desc, B);
+    if (want_params || fused_dx) {
         const ChunkPlan cp = bp.cp;
         char *at = (char *)ws + folded_bytes(desc);
         void *walk_scratch = at;
@@ -153,12 +160,13 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         float *part_c = (float *)at;
         float *part_b = (float *)((char *)part_c + (size_t)cp.n_chunks * folded_bytes(desc));
         // partial slabs are laid out back to back with the unpadded slab size
-        hipError_t e = bp.walk ? launch_dparam_walk(g, bp.wp, x, gy, walk_scratch, part_c, want_b ? part_b : nullptr,
-                                                    B, st)
+        hipError_t e = bp.walk ? launch_backward_walk(g, bp.wp, x, gy, cf, w_b, walk_scratch, fused_dx ? gx : nullptr,
+                                                      want_params ? part_c : nullptr, want_b ? part_b : nullptr, B, st)
                                : launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks,
                                                        cp.chunk_len, st);
         if (e != hipSuccess) return KAN_ERR_HIP;
-        if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
+        if (want_params &&
+            launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
                                  g.n_out, cp.n_chunks, cp.n_chunks * bp.b_slices_per_chunk, st) != hipSuccess)
             return KAN_ERR_HIP;
     }

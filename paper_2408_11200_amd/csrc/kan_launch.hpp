@@ -74,8 +74,9 @@ struct WalkPlan {
 };
 WalkPlan plan_walk(const SplineGeom &g, int64_t B);
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in);
-hipError_t launch_dparam_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy, void *scratch,
-                              float *part_c, float *part_b, int64_t B, hipStream_t st);
+hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,
+                                const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,
+                                float *part_b, int64_t B, hipStream_t st);
 
 // How the batch is cut into chunks for the parameter-gradient reduction: chunks of about 1024
 // samples, at most 64 of them, and no more than fit a 512 MiB budget of partial sums.

@@ -57,7 +57,8 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
 // Entries past the end of the batch get the largest row and end up behind every real record.
 __global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, const float *__restrict__ xT, int64_t B,
                                                                  int S, int sbits, int row_bits,
-                                                                 PairRecord *__restrict__ rec)
+                                                                 PairRecord *__restrict__ rec,
+                                                                 PairRecord *__restrict__ rec_d)
 {
     extern __shared__ unsigned lds_u[];
     unsigned *src = lds_u, *dst = lds_u + S;
@@ -129,22 +130,24 @@ __global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, c
         unsigned *t = src; src = dst; dst = t;
     }
 
-    PairRecord *out = rec + ((int64_t)c * g.n_in + i) * S;
+    const int64_t list = ((int64_t)c * g.n_in + i) * S;
     for (int p = tid; p < S; p += kSortThreads) {
         const int e = (int)(src[p] & (unsigned)(S - 1));
         const bool live = e < n_c;
-        const Pair pr = pair_eval<false>(xs[e], g, i);
-        PairRecord r;
+        const Pair pr = rec_d ? pair_eval<true>(xs[e], g, i) : pair_eval<false>(xs[e], g, i);
+        PairRecord r, rd;
         int row0;
         window_of<false>(pr, g.rows, row0, r.w, r.base);
+        window_of<true>(pr, g.rows, row0, rd.w, rd.base);
         if (!live) {
             row0 = g.rows - kMaxK;
 #pragma unroll
-            for (int s = 0; s < kMaxK; ++s) r.w[s] = 0.0f;
-            r.base = 0.0f;
+            for (int s = 0; s < kMaxK; ++s) { r.w[s] = 0.0f; rd.w[s] = 0.0f; }
+            r.base = 0.0f; rd.base = 0.0f;
         }
-        r.rt = row0 | ((live ? e : 0) << 16);
-        out[p] = r;
+        r.rt = rd.rt = row0 | ((live ? e : 0) << 16);
+        rec[list + p] = r;
+        if (rec_d) rec_d[list + p] = rd;
     }
 }
 
@@ -158,6 +161,53 @@ template <int N>
 __device__ __forceinline__ float row_bcast(float v)
 {
     return __builtin_bit_cast(float, row_bcast<N>(__builtin_bit_cast(int, v)));
+}
+
+// value of the partner lane for the level that pairs lanes differing in bit D (for D = 4 the partner
+// is lane ^ 7: it differs in bit 2, which is all the reduction below needs)
+template <int D>
+__device__ __forceinline__ float partner(float v)
+{
+    const int iv = __builtin_bit_cast(int, v);
+    if constexpr (D >= 16) return __shfl_xor(v, D, 64);
+    else if constexpr (D == 8) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0x128, 0xF, 0xF, true));
+    else if constexpr (D == 4) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0x141, 0xF, 0xF, true));
+    else if constexpr (D == 2) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0x4E, 0xF, 0xF, true));
+    else return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, 0xB1, 0xF, 0xF, true));
+}
+
+// p[0..N) hold, per lane, partial sums of N quantities.  Sums them over groups of LPS lanes while
+// halving the number of quantities a lane carries at each level (lanes whose bit D is set keep the
+// upper half); once one is left the remaining levels are plain sums.  Returns the total of quantity
+// number quantity_of<LPS>(lane).
+template <int D, int N>
+__device__ __forceinline__ float reduce_levels(float (&p)[N], int lane)
+{
+    if constexpr (N > 1) {
+        const bool up = (lane & D) != 0;
+        float h[N / 2];
+#pragma unroll
+        for (int k = 0; k < N / 2; ++k) {
+            const float keep = up ? p[k + N / 2] : p[k];
+            const float send = up ? p[k] : p[k + N / 2];
+            h[k] = keep + partner<D>(send);
+        }
+        if constexpr (D > 1) return reduce_levels<D / 2, N / 2>(h, lane);
+        else return h[0];
+    } else {
+        float v = p[0] + partner<D>(p[0]);
+        if constexpr (D > 1) {
+            float one[1] = {v};
+            return reduce_levels<D / 2, 1>(one, lane);
+        } else {
+            return v;
+        }
+    }
+}
+template <int LPS>
+__device__ __forceinline__ int quantity_of(int lane)      // 16 quantities: the top four levels select
+{
+    return (lane / (LPS / 16)) & 15;
 }
 
 template <int N, int END, class F>
@@ -187,16 +237,26 @@ __device__ __forceinline__ void store_vec(float *p, const float (&v)[T])
     else p[0] = v[0];
 }
 
-// 4 waves per block, STREAMS streams per wave; stream number w = ((chunk * n_jt) + jt) * n_in + i,
-// so that the streams of a wave gather gy rows of the same chunk.  Per record: one gather of the
-// sample's gy row (T floats per lane), K + 1 broadcasts, (K + 1) * T multiply-adds.  Sums are kept
-// in two levels (the running sums are folded into a second set every 256 records) so that a long
-// run of samples in one cell does not lose accuracy to sequential fp32 accumulation.
-template <int STREAMS, int T>
-__global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const PairRecord *__restrict__ rec,
-                                                          const float *__restrict__ gy, float *__restrict__ part_c,
-                                                          float *__restrict__ part_b, int64_t B, int S, int n_chunks,
-                                                          int n_jt, int blocks_per_chunk, int xcd_groups)
+// 4 waves per block, STREAMS streams per wave.  Per record: one gather of the sample's gy row
+// (T floats per lane), K + 1 broadcasts, (K + 1) * T multiply-adds.  Sums are kept in two levels
+// (the running sums are folded into a second set every 256 records) so that a long run of samples
+// in one cell does not lose accuracy to sequential fp32 accumulation.
+//
+// DX: the same walk also produces dL/dx.  The K rows of the scale-folded table under the window
+// slide along in registers with the accumulators (one row is loaded per step of the window), so a
+// record costs another (K + 1) * T multiply-adds for  q_j = sum_s dw_s c[row+s][j] + dbase w_b[j]
+// and T for gy . q; the per-lane partial dot products of 16 records are summed over the stream's lanes
+// together (reduce_levels) and scattered to gx[sample][i] (gx_part[jt] when the layer has several
+// output tiles; those are added up by gx_sum_kernel).
+template <int STREAMS, int T, bool DX>
+__global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const PairRecord *__restrict__ rec,
+                                                            const PairRecord *__restrict__ rec_d,
+                                                            const float *__restrict__ gy,
+                                                            const float *__restrict__ cf,
+                                                            const float *__restrict__ w_b,
+                                                            float *__restrict__ part_c, float *__restrict__ part_b,
+                                                            float *__restrict__ gx, int64_t B, int S, int n_chunks,
+                                                            int n_jt, int blocks_per_chunk, int xcd_groups)
 {
     constexpr int LPS = 64 / STREAMS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -219,8 +279,12 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
     const int64_t b0 = (int64_t)c * S;
     const int n_c = (int)((B - b0) < S ? (B - b0) : S);
     const PairRecord *list = rec + ((int64_t)c * g.n_in + i) * S;
+    const PairRecord *list_d = DX ? rec_d + ((int64_t)c * g.n_in + i) * S : nullptr;
     const float *gyp = gy + b0 * g.n_out + jc;
+    const bool store_c = jok && part_c != nullptr;
     float *out = part_c + ((int64_t)c * g.n_in + i) * g.rows * g.n_out + jc;
+    const float *cfi = DX ? cf + (int64_t)i * g.slab_rows * g.n_out + jc : nullptr;
+    float *gxo = DX ? gx + (int64_t)jt * B * g.n_in + b0 * g.n_in + i : nullptr;
 
     float a[kMaxK][T], hi[kMaxK][T], ab[T], abh[T], zero[T];
 #pragma unroll
@@ -231,14 +295,34 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
     }
 
     int cur = list[0].rt & 0xffff;           // first row of the window the accumulators stand on
-    if (jok)
+    if (store_c)
         for (int m = 0; m < cur; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
 
+    // dL/dx: table rows cur .. cur+K-1 and the w_b row, zero in lanes past the last output
+    float cw[kMaxK][T], wb[T];
+    const float jmask = jok ? 1.0f : 0.0f;
+    if constexpr (DX) {
+#pragma unroll
+        for (int r = 0; r < T; ++r) wb[r] = 0.0f;
+        if (jok && w_b != nullptr && g.base_act != 0) load_vec<T>(w_b + (int64_t)i * g.n_out + j, wb);
+#pragma unroll
+        for (int s = 0; s < kMaxK; ++s) {
+            load_vec<T>(cfi + (int64_t)(cur + s) * g.n_out, cw[s]);
+#pragma unroll
+            for (int r = 0; r < T; ++r) cw[s][r] *= jmask;
+        }
+    }
+
     const int nb = (n_c + 15) / 16;
-    PairRecord mine = list[r16];
+    PairRecord mine = list[r16], mine_d;
+    if constexpr (DX) mine_d = list_d[r16];
     for (int bi = 0; bi < nb; ++bi) {
-        const PairRecord upcoming = list[(bi + 1 < nb ? bi + 1 : bi) * 16 + r16];
+        const int nxt = (bi + 1 < nb ? bi + 1 : bi) * 16 + r16;
+        const PairRecord upcoming = list[nxt];
+        PairRecord upcoming_d;
+        if constexpr (DX) upcoming_d = list_d[nxt];
         const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
+        float dot[16];
         auto half = [&](auto h) {
             constexpr int H = decltype(h)::value;
             float gr[8][T];
@@ -249,9 +333,10 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
             });
             static_for<0, 8>([&](auto n) {
                 constexpr int N = decltype(n)::value;
-                const int row0 = row_bcast<H * 8 + N>(rowv);
-                while (cur < row0) {            // the window moves on: its first row is complete
-                    if (jok) {
+                constexpr int R = H * 8 + N;
+                const int row0 = row_bcast<R>(rowv);
+                auto advance = [&]() {          // the window moves on: its first row is complete
+                    if (store_c) {
                         float o[T];
 #pragma unroll
                         for (int r = 0; r < T; ++r) o[r] = a[0][r] + hi[0][r];
@@ -264,10 +349,28 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
                         a[kMaxK - 1][r] = 0.0f; hi[kMaxK - 1][r] = 0.0f;
                     }
                     ++cur;
+                    if constexpr (DX) {
+#pragma unroll
+                        for (int r = 0; r < T; ++r) {
+#pragma unroll
+                            for (int s = 0; s + 1 < kMaxK; ++s) cw[s][r] = cw[s + 1][r];
+                        }
+                        load_vec<T>(cfi + (int64_t)(cur + kMaxK - 1) * g.n_out, cw[kMaxK - 1]);
+#pragma unroll
+                        for (int r = 0; r < T; ++r) cw[kMaxK - 1][r] *= jmask;
+                    }
+                };
+                // (the compiler peels this loop; with the dL/dx state on top that costs more registers
+                // than it saves instructions)
+                if constexpr (DX) {
+#pragma clang loop unroll(disable)
+                    while (cur < row0) advance();
+                } else {
+                    while (cur < row0) advance();
                 }
-                const float w0 = row_bcast<H * 8 + N>(mine.w[0]), w1 = row_bcast<H * 8 + N>(mine.w[1]);
-                const float w2 = row_bcast<H * 8 + N>(mine.w[2]), w3 = row_bcast<H * 8 + N>(mine.w[3]);
-                const float bs = row_bcast<H * 8 + N>(mine.base);
+                const float w0 = row_bcast<R>(mine.w[0]), w1 = row_bcast<R>(mine.w[1]);
+                const float w2 = row_bcast<R>(mine.w[2]), w3 = row_bcast<R>(mine.w[3]);
+                const float bs = row_bcast<R>(mine.base);
 #pragma unroll
                 for (int r = 0; r < T; ++r) {
                     a[0][r] = fmaf(w0, gr[N][r], a[0][r]);
@@ -276,10 +379,35 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
                     a[3][r] = fmaf(w3, gr[N][r], a[3][r]);
                     ab[r] = fmaf(bs, gr[N][r], ab[r]);
                 }
+                if constexpr (DX) {
+                    const float d0 = row_bcast<R>(mine_d.w[0]), d1 = row_bcast<R>(mine_d.w[1]);
+                    const float d2 = row_bcast<R>(mine_d.w[2]), d3 = row_bcast<R>(mine_d.w[3]);
+                    const float db = row_bcast<R>(mine_d.base);
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < T; ++r) {
+                        float qv = d0 * cw[0][r];
+                        qv = fmaf(d1, cw[1][r], qv);
+                        qv = fmaf(d2, cw[2][r], qv);
+                        qv = fmaf(d3, cw[3][r], qv);
+                        qv = fmaf(db, wb[r], qv);
+                        acc = fmaf(gr[N][r], qv, acc);
+                    }
+                    // pin the dot product here: left alone, the compiler sinks all sixteen of them below the
+                    // last record and keeps a copy of the table rows per record alive until then
+                    asm volatile("" : "+v"(acc));
+                    dot[R] = acc;
+                }
             });
         };
         half(std::integral_constant<int, 0>{});
         half(std::integral_constant<int, 1>{});
+        if constexpr (DX) {
+            const float total = reduce_levels<LPS / 2, 16>(dot, lane);
+            const int qn = quantity_of<LPS>(lane);
+            const int t = __shfl(tv, (lane & ~15) | qn, 64);
+            if ((lane % (LPS / 16)) == 0 && bi * 16 + qn < n_c) gxo[(int64_t)t * g.n_in] = total;
+        }
         if ((bi & 15) == 15) {
 #pragma unroll
             for (int r = 0; r < T; ++r) {
@@ -289,9 +417,10 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
             }
         }
         mine = upcoming;
+        if constexpr (DX) mine_d = upcoming_d;
     }
 
-    if (!jok) return;
+    if (!store_c) return;
 #pragma unroll
     for (int s = 0; s < kMaxK; ++s) {
         float o[T];
@@ -306,6 +435,17 @@ __global__ __launch_bounds__(256) void dparam_walk_kernel(SplineGeom g, const Pa
         for (int r = 0; r < T; ++r) o[r] = ab[r] + abh[r];
         store_vec<T>(part_b + ((int64_t)c * g.n_in + i) * g.n_out + jc, o);
     }
+}
+
+// gx = sum over the output tiles' partial gx
+__global__ __launch_bounds__(256) void gx_sum_kernel(const float *__restrict__ part, float *__restrict__ gx, int64_t n,
+                                                     int n_jt)
+{
+    const int64_t at = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (at >= n) return;
+    float v = part[at];
+    for (int t = 1; t < n_jt; ++t) v += part[(int64_t)t * n + at];
+    gx[at] = v;
 }
 
 int log2_exact(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
@@ -352,17 +492,43 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
     return p;
 }
 
-size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
-{
-    const size_t xt = ((size_t)B * n_in * sizeof(float) + 255) / 256 * 256;
-    return xt + (size_t)p.n_chunks * n_in * p.S * sizeof(PairRecord);
+namespace {
+size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 }
 
-hipError_t launch_dparam_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy, void *scratch,
-                              float *part_c, float *part_b, int64_t B, hipStream_t st)
+// transposed x | value records | derivative records | per-tile partial gx (layers wider than one tile)
+size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
 {
+    const size_t recs = up256((size_t)p.n_chunks * n_in * p.S * sizeof(PairRecord));
+    const size_t gxp = p.n_jt > 1 ? up256((size_t)p.n_jt * B * n_in * sizeof(float)) : 0;
+    return up256((size_t)B * n_in * sizeof(float)) + 2 * recs + gxp;
+}
+
+template <int STREAMS, int T>
+static void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const PairRecord *rec,
+                        const PairRecord *rec_d, const float *gy, const float *cf, const float *w_b, float *part_c,
+                        float *part_b, float *gx, int64_t B, const WalkPlan &p, int bpc, int m)
+{
+    if (dx)
+        backward_walk_kernel<STREAMS, T, true><<<blocks, 256, 0, st>>>(g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx, B,
+                                                                      p.S, p.n_chunks, p.n_jt, bpc, m);
+    else
+        backward_walk_kernel<STREAMS, T, false><<<blocks, 256, 0, st>>>(g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx, B,
+                                                                       p.S, p.n_chunks, p.n_jt, bpc, m);
+}
+
+// gx == nullptr: parameter gradients only.  part_c == nullptr: dL/dx only.  cf is the scale-folded
+// table ([n_in][slab_rows][n_out]); w_b may be null when the layer has no base term.
+hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,
+                                const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,
+                                float *part_b, int64_t B, hipStream_t st)
+{
+    const size_t recs = up256((size_t)p.n_chunks * g.n_in * p.S * sizeof(PairRecord));
     float *xT = (float *)scratch;
-    PairRecord *rec = (PairRecord *)((char *)scratch + ((size_t)B * g.n_in * sizeof(float) + 255) / 256 * 256);
+    PairRecord *rec = (PairRecord *)((char *)scratch + up256((size_t)B * g.n_in * sizeof(float)));
+    PairRecord *rec_d = (PairRecord *)((char *)rec + recs);
+    float *gx_part = (float *)((char *)rec_d + recs);
+    const bool dx = gx != nullptr;
     {
         dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
         prof::Timed tm("walk_transpose", st);
@@ -375,24 +541,33 @@ hipError_t launch_dparam_walk(const SplineGeom &g, const WalkPlan &p, const floa
         if (e != hipSuccess) return e;
         dim3 grid((unsigned)p.n_chunks, (unsigned)g.n_in);
         prof::Timed tm("walk_sort", st);
-        cell_sort_kernel<<<grid, kSortThreads, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec);
+        cell_sort_kernel<<<grid, kSortThreads, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec,
+                                                          dx ? rec_d : nullptr);
     }
     const int bpc = (p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
     int m = 1;
     while (m * 2 <= 8 && m * 2 <= p.n_chunks) m *= 2;
     const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
     const unsigned blocks = (unsigned)(8 * bpc_sub * ((p.n_chunks + m - 1) / m));
-    prof::Timed tm("dparam_walk", st);
-    if (p.T == 4 && p.streams == 1)
-        dparam_walk_kernel<1, 4><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
-    else if (p.T == 4 && p.streams == 2)
-        dparam_walk_kernel<2, 4><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
-    else if (p.T == 4 && p.streams == 4)
-        dparam_walk_kernel<4, 4><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
-    else if (p.T == 1 && p.streams == 4)
-        dparam_walk_kernel<4, 1><<<blocks, 256, 0, st>>>(g, rec, gy, part_c, part_b, B, p.S, p.n_chunks, p.n_jt, bpc, m);
-    else
-        return hipErrorInvalidValue;
+    float *gx_out = dx ? (p.n_jt > 1 ? gx_part : gx) : nullptr;
+    {
+        prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
+        if (p.T == 4 && p.streams == 1)
+            walk_launch<1, 4>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+        else if (p.T == 4 && p.streams == 2)
+            walk_launch<2, 4>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+        else if (p.T == 4 && p.streams == 4)
+            walk_launch<4, 4>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+        else if (p.T == 1 && p.streams == 4)
+            walk_launch<4, 1>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+        else
+            return hipErrorInvalidValue;
+    }
+    if (dx && p.n_jt > 1) {
+        const int64_t n = B * g.n_in;
+        prof::Timed tm("walk_gx_sum", st);
+        gx_sum_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(gx_part, gx, n, p.n_jt);
+    }
     return hipGetLastError();
 }
 

@@ -205,7 +205,9 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     const int64_t rows = (int64_t)desc->n_in * pr.n_g, n_o = (int64_t)K * desc->n_out;
 
     const bool narrow = narrow_applicable(pr.g) != 0;
-    if (gx) {
+    const WalkPlan wp = walk_for(desc, B, max_groups);
+    const bool fused_dx = gx && wp.ok;      // dL/dx rides along with the table gradient
+    if (gx && !fused_dx) {
         hipError_t e = narrow ? launch_dx_narrow(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st)
                               : launch_dx_generic(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st);
         if (e != hipSuccess) return KAN_ERR_HIP;
@@ -213,15 +215,16 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
 
     const bool cg_grads = g && (g->gE || g->gW1 || g->gb1 || g->gW2 || g->gb2);
     const bool want_b = g && g->gw_b && desc->base_act != KAN_BASE_NONE;
-    if (!(cg_grads || (g && (g->gscale || g->gw_b)))) return KAN_OK;
+    const bool want_params = cg_grads || (g && (g->gscale || g->gw_b));
+    if (!want_params && !fused_dx) return KAN_OK;
 
     // table gradient: partial sums per batch chunk, then  gout = scale * sum,  gscale = sum_m raw * sum
     float *part_c = (float *)(w + L.part_c), *part_b = (float *)(w + L.part_b);
     float *gout = (float *)(w + L.gout);
-    const WalkPlan wp = walk_for(desc, B, max_groups);
     int b_slices;
     if (wp.ok) {
-        if (launch_dparam_walk(pr.g, wp, x, gy, w + L.rec, part_c, want_b ? part_b : nullptr, B, st) != hipSuccess)
+        if (launch_backward_walk(pr.g, wp, x, gy, (const float *)(w + L.cf), p->w_b, w + L.rec, fused_dx ? gx : nullptr,
+                                 want_params ? part_c : nullptr, want_b ? part_b : nullptr, B, st) != hipSuccess)
             return KAN_ERR_HIP;
         b_slices = pr.cp.n_chunks;
     } else {
@@ -230,6 +233,7 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
             return KAN_ERR_HIP;
         b_slices = pr.cp.n_chunks * dparam_generic_row_blocks(pr.g.rows);
     }
+    if (!want_params) return KAN_OK;
     if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
                              cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,
                              pr.cp.n_chunks, b_slices, st) != hipSuccess)

@@ -246,7 +246,7 @@ def ukan_cg_forward(spec, x, p, max_groups, y=None, ws=None, stream=None):
     return y
 
 
-def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, ws=None, stream=None):
+def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, stream=None):
     lib = load()
     d = ukan_desc(spec)
     B = x.shape[0]
@@ -257,7 +257,8 @@ def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, ws=None, stream=None
               "gscale": (spec.n_in, spec.n_out), "gw_b": (spec.n_in, spec.n_out)}
     if want is None:
         want = [n for n in shapes if n != "gw_b" or spec.base_act]
-    out = {n: torch.empty(shapes[n], dtype=torch.float32, device=x.device) for n in want}
+    if out is None:
+        out = {n: torch.empty(shapes[n], dtype=torch.float32, device=x.device) for n in want}
     if ws is None:
         ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_BACKWARD), x.device)
     pp = _ukan_params(p)

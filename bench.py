@@ -32,6 +32,7 @@ def flops_per_edge(k):
 MEASURED_TRAFFIC_BYTES_C3 = {
     "forward_lds": 235.3e6 + 33.6e6,
     "dx_lds": 268.5e6 + 33.6e6,
+    "dparam_walk": 437.0e6 + 402.7e6,
 }
 
 # kernel family -> which third of the fwd+bwd work it carries ("backward" = dL/dx and the parameter

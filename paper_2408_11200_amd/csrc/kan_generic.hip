@@ -133,18 +133,18 @@ __global__ __launch_bounds__(256) void forward_generic_kernel(SplineGeom g, cons
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const int src = ii * T + t;
+                // no branch on "window outside the table": those weights are zero and the rows are
+                // clamped, so the loads of all T samples can be in flight together
                 const int cell = lane_i(p.cell, src);
-                if (cell > -kMaxK && cell < g.rows) {       // uniform: some weight is non-zero
-                    float c[kMaxK][R];
+                float c[kMaxK][R];
 #pragma unroll
-                    for (int s = 0; s < kMaxK; ++s)
-                        load_vec<R>(slab + (int64_t)clampi(cell + s, 0, g.rows - 1) * g.n_out, c[s]);
+                for (int s = 0; s < kMaxK; ++s)
+                    load_vec<R>(slab + (int64_t)clampi(cell + s, 0, g.rows - 1) * g.n_out, c[s]);
 #pragma unroll
-                    for (int s = 0; s < kMaxK; ++s) {
-                        const float ws = lane_f(p.w[s], src);
+                for (int s = 0; s < kMaxK; ++s) {
+                    const float ws = lane_f(p.w[s], src);
 #pragma unroll
-                        for (int r = 0; r < R; ++r) acc[t][r] = fmaf(ws, c[s][r], acc[t][r]);
-                    }
+                    for (int r = 0; r < R; ++r) acc[t][r] = fmaf(ws, c[s][r], acc[t][r]);
                 }
                 if (g.base_act) {
                     const float bs = lane_f(p.base, src);
@@ -480,15 +480,30 @@ hipError_t launch_fold_scale(const float *coef, const float *w_s, const float *w
     return hipGetLastError();
 }
 
-template <int R>
-static hipError_t forward_r(const SplineGeom &g, const float *x, const float *cf, const float *w_b, float *y,
-                            int64_t B, hipStream_t st)
+template <int R, int T>
+static hipError_t forward_rt(const SplineGeom &g, const float *x, const float *cf, const float *w_b, float *y,
+                             int64_t B, hipStream_t st)
 {
-    constexpr int T = (R == 4) ? 8 : 16;
     dim3 grid((unsigned)((B + 4 * T - 1) / (4 * T)), (unsigned)((g.n_out + 64 * R - 1) / (64 * R)));
     prof::Timed tm("forward_generic", st);
     forward_generic_kernel<R, T><<<grid, 256, 0, st>>>(g, x, cf, w_b, y, B);
     return hipGetLastError();
+}
+
+// samples per wave: as many as still leave the chip about four waves per SIMD (the kernel lives on
+// loads in flight), between 2 and 8 (16 for the one- and two-output-per-lane variants)
+template <int R>
+static hipError_t forward_r(const SplineGeom &g, const float *x, const float *cf, const float *w_b, float *y,
+                            int64_t B, hipStream_t st)
+{
+    const int64_t tiles = (g.n_out + 64 * R - 1) / (64 * R);
+    auto waves = [&](int t) { return (B + t - 1) / t * tiles; };
+    if constexpr (R != 4) {
+        if (waves(16) >= 4096) return forward_rt<R, 16>(g, x, cf, w_b, y, B, st);
+    }
+    if (waves(8) >= 4096) return forward_rt<R, 8>(g, x, cf, w_b, y, B, st);
+    if (waves(4) >= 4096) return forward_rt<R, 4>(g, x, cf, w_b, y, B, st);
+    return forward_rt<R, 2>(g, x, cf, w_b, y, B, st);
 }
 
 hipError_t launch_forward_generic(const SplineGeom &g, const float *x, const float *cf, const float *w_b,

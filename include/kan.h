@@ -14,7 +14,8 @@
  *     the matching *_workspace_bytes call returns (256-byte aligned).
  *   - `stream` is a hipStream_t passed as void*.  All work is enqueued on it.
  *     kan_* calls never synchronise; the ukan_* calls synchronise the stream
- *     once to read back the group span (8 bytes), see below.
+ *     once to read back the group span (4 bytes), see below.
+ *   - Every float array must be 16-byte aligned (KAN_ERR_INVALID_ARG otherwise).
  *   - Row-major layouts:  x[B][n_in]  y,gy[B][n_out]  gx[B][n_in]
  *       coef,gcoef[n_in][G+k][n_out]   w_s,w_b,gw_s,gw_b[n_in][n_out]
  *   - Return value: KAN_OK or a negative kan_status; nothing is thrown.  B == 0
@@ -44,7 +45,7 @@ extern "C" {
 
 typedef enum kan_status {
     KAN_OK = 0,
-    KAN_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, grid_hi <= grid_lo, h <= 0 */
+    KAN_ERR_INVALID_ARG = -1, /* null or misaligned pointer, non-positive size, grid_hi <= grid_lo, h <= 0 */
     KAN_ERR_UNSUPPORTED = -2, /* k outside 1..3, unknown base_act, CG widths not supported    */
     KAN_ERR_WORKSPACE = -3,   /* ws is NULL / misaligned / smaller than *_workspace_bytes     */
     KAN_ERR_RANGE = -4,       /* UKAN: some input spans more groups than max_groups           */

@@ -10,6 +10,9 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+// every float array is read and written with 16-byte accesses where the widths allow
+inline bool misaligned(const void *p) { return p && ((uintptr_t)p % 16) != 0; }
+
 int check_desc(const kan_layer_desc *d)
 {
     if (!d) return KAN_ERR_INVALID_ARG;
@@ -109,6 +112,7 @@ extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x
     if (B == 0) return KAN_OK;
     if (!x || !coef || !w_s || !y) return KAN_ERR_INVALID_ARG;
     if (desc->base_act != KAN_BASE_NONE && !w_b) return KAN_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(coef) || misaligned(w_s) || misaligned(w_b) || misaligned(y)) return KAN_ERR_INVALID_ARG;
     if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < kan_workspace_bytes(desc, B, KAN_PASS_FORWARD))
         return KAN_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
@@ -131,6 +135,9 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     if (B == 0) return KAN_OK;
     if (!x || !coef || !w_s || !gy) return KAN_ERR_INVALID_ARG;
     if (desc->base_act != KAN_BASE_NONE && !w_b) return KAN_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(coef) || misaligned(w_s) || misaligned(w_b) || misaligned(gy) || misaligned(gx) ||
+        misaligned(gcoef) || misaligned(gw_s) || misaligned(gw_b))
+        return KAN_ERR_INVALID_ARG;
     if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < kan_workspace_bytes(desc, B, KAN_PASS_BACKWARD))
         return KAN_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;

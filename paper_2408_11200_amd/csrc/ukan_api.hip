@@ -1,6 +1,7 @@
 // C ABI of the UKAN layer: workspace layout, the single read-back of the group span, and
 // the sequence of kernels (range -> CG forward -> spline kernels -> CG backward).
 // See include/kan.h for the contract.
+#include <initializer_list>
 #include "kan.h"
 #include "kan_launch.hpp"
 #include "ukan_launch.hpp"
@@ -156,6 +157,9 @@ int check_common(const ukan_layer_desc *d, int64_t B, const float *x, const ukan
     if (B == 0) return KAN_OK;
     if (!x || !p || !p->E || !p->W1 || !p->b1 || !p->W2 || !p->b2 || !p->scale) return KAN_ERR_INVALID_ARG;
     if (d->base_act != KAN_BASE_NONE && !p->w_b) return KAN_ERR_INVALID_ARG;
+    for (const void *q : {(const void *)x, (const void *)p->E, (const void *)p->W1, (const void *)p->b1,
+                          (const void *)p->W2, (const void *)p->b2, (const void *)p->scale, (const void *)p->w_b})
+        if (q && ((uintptr_t)q % 16) != 0) return KAN_ERR_INVALID_ARG;
     size_t need = ukan_workspace_bytes(d, B, max_groups, pass);
     if (!ws || ((uintptr_t)ws % kAlign) != 0 || need == 0 || ws_bytes < need) return KAN_ERR_WORKSPACE;
     return KAN_OK;
@@ -176,7 +180,7 @@ extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const flo
 {
     int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_FORWARD);
     if (rc != KAN_OK || B == 0) return rc;
-    if (!y) return KAN_ERR_INVALID_ARG;
+    if (!y || ((uintptr_t)y % 16) != 0) return KAN_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     Prepared pr;
     rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr);
@@ -194,7 +198,11 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
 {
     int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_BACKWARD);
     if (rc != KAN_OK || B == 0) return rc;
-    if (!gy) return KAN_ERR_INVALID_ARG;
+    if (!gy || ((uintptr_t)gy % 16) != 0 || ((uintptr_t)gx % 16) != 0) return KAN_ERR_INVALID_ARG;
+    if (g)
+        for (const void *q : {(const void *)g->gE, (const void *)g->gW1, (const void *)g->gb1, (const void *)g->gW2,
+                              (const void *)g->gb2, (const void *)g->gscale, (const void *)g->gw_b})
+            if (q && ((uintptr_t)q % 16) != 0) return KAN_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     char *w = (char *)ws;
     Prepared pr;

@@ -55,12 +55,16 @@ int dx_lds_plan(const SplineGeom &g);
 hipError_t launch_dx_lds(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx, int64_t B,
                          hipStream_t st);
 
-// One record per (sample, input) pair: first row of the K-wide window (clamped into the table),
-// the sample's index inside its chunk, the K window weights and the base value.
-struct PairRecord {
-    int rt;             // first window row | sample index in the chunk << 16
-    float w[kMaxK];
-    float base;
+// Sorted pair records of the walk, one per (sample, input) pair, as a structure of arrays indexed
+// [chunk][input][rank in the chunk's sorted order]: first row of the K-wide window (clamped into the
+// table) | the sample's index inside its chunk << 16; the base value; the K window weights (16-byte
+// aligned quadruples); and the same for the x-derivatives (null when dL/dx is not wanted).
+struct WalkRecords {
+    int *rt;
+    float *base;
+    float *w4;
+    float *dbase;
+    float *dw4;
 };
 
 // Chunk-sorted walk (large grids, narrow layers).  plan_walk().ok == 0: shape not covered.

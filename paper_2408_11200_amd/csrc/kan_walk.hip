@@ -14,7 +14,8 @@
 //
 //   1. transpose_kernel     x[B][n_in] -> xT[n_in][B], so that one input's samples are contiguous
 //   2. cell_sort_kernel     per (chunk, input): stable LSD radix sort of the S samples by window row
-//                           in LDS, then one PairRecord per sample in sorted order
+//                           in LDS, then one record per sample in sorted order (structure of
+//                           arrays: window row | sample, base value, the K weights)
 //   3. dparam_walk_kernel   the walk; partial sums per chunk, reduced by dparam_reduce (fp64,
 //                           fixed order), so results are bit-reproducible
 //
@@ -22,6 +23,13 @@
 // narrow layers still fill the wave.  Records are loaded 16 at a time, one per lane of each DPP row
 // of 16 lanes, and broadcast inside the row with row_newbcast; there is no scalar state, hence
 // streams in one wave may diverge freely.
+//
+// The accumulation itself, acc[row s][output j] += w_s * gy[j] for the K = 4 window rows, is a
+// rank-1 update, and runs on the matrix cores as v_mfma_f32_4x4x1 (16 blocks of 4x4 outer
+// products): a lane's B operand is gy of its output, the A operand of every block is the weight
+// quadruple of the current record, which the instruction itself broadcasts from the four lanes that
+// hold it (cbsz / abid), so the weights of 16 records are one coalesced 256-byte load and cost no
+// VALU work.  None of the 256 multiply-adds of an instruction is padding.
 #include <type_traits>
 #include "kan_device.hpp"
 #include "kan_launch.hpp"
@@ -56,9 +64,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
 // keys batch by batch (rank inside a batch from ballots), so nothing depends on timing.
 // Entries past the end of the batch get the largest row and end up behind every real record.
 __global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, const float *__restrict__ xT, int64_t B,
-                                                                 int S, int sbits, int row_bits,
-                                                                 PairRecord *__restrict__ rec,
-                                                                 PairRecord *__restrict__ rec_d)
+                                                                 int S, int sbits, int row_bits, WalkRecords rec)
 {
     extern __shared__ unsigned lds_u[];
     unsigned *src = lds_u, *dst = lds_u + S;
@@ -134,20 +140,24 @@ __global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, c
     for (int p = tid; p < S; p += kSortThreads) {
         const int e = (int)(src[p] & (unsigned)(S - 1));
         const bool live = e < n_c;
-        const Pair pr = rec_d ? pair_eval<true>(xs[e], g, i) : pair_eval<false>(xs[e], g, i);
-        PairRecord r, rd;
+        const Pair pr = rec.dw4 ? pair_eval<true>(xs[e], g, i) : pair_eval<false>(xs[e], g, i);
+        float w[kMaxK], dw[kMaxK], base, dbase;
         int row0;
-        window_of<false>(pr, g.rows, row0, r.w, r.base);
-        window_of<true>(pr, g.rows, row0, rd.w, rd.base);
+        window_of<false>(pr, g.rows, row0, w, base);
+        window_of<true>(pr, g.rows, row0, dw, dbase);
         if (!live) {
             row0 = g.rows - kMaxK;
 #pragma unroll
-            for (int s = 0; s < kMaxK; ++s) { r.w[s] = 0.0f; rd.w[s] = 0.0f; }
-            r.base = 0.0f; rd.base = 0.0f;
+            for (int s = 0; s < kMaxK; ++s) { w[s] = 0.0f; dw[s] = 0.0f; }
+            base = 0.0f; dbase = 0.0f;
         }
-        r.rt = rd.rt = row0 | ((live ? e : 0) << 16);
-        rec[list + p] = r;
-        if (rec_d) rec_d[list + p] = rd;
+        rec.rt[list + p] = row0 | ((live ? e : 0) << 16);
+        rec.base[list + p] = base;
+        *reinterpret_cast<float4 *>(rec.w4 + (list + p) * 4) = make_float4(w[0], w[1], w[2], w[3]);
+        if (rec.dw4) {
+            rec.dbase[list + p] = dbase;
+            *reinterpret_cast<float4 *>(rec.dw4 + (list + p) * 4) = make_float4(dw[0], dw[1], dw[2], dw[3]);
+        }
     }
 }
 
@@ -238,9 +248,10 @@ __device__ __forceinline__ void store_vec(float *p, const float (&v)[T])
 }
 
 // 4 waves per block, STREAMS streams per wave.  Per record: one gather of the sample's gy row
-// (T floats per lane), K + 1 broadcasts, (K + 1) * T multiply-adds.  Sums are kept in two levels
-// (the running sums are folded into a second set every 256 records) so that a long run of samples
-// in one cell does not lose accuracy to sequential fp32 accumulation.
+// (T floats per lane), T matrix-core instructions for the K window rows, T multiply-adds for the
+// base term.  Sums are kept in two levels (the running sums are folded into a second set every 256
+// records) so that a long run of samples in one cell does not lose accuracy to sequential fp32
+// accumulation.
 //
 // DX: the same walk also produces dL/dx.  The K rows of the scale-folded table under the window
 // slide along in registers with the accumulators (one row is loaded per step of the window), so a
@@ -248,9 +259,18 @@ __device__ __forceinline__ void store_vec(float *p, const float (&v)[T])
 // and T for gy . q; the per-lane partial dot products of 16 records are summed over the stream's lanes
 // together (reduce_levels) and scattered to gx[sample][i] (gx_part[jt] when the layer has several
 // output tiles; those are added up by gx_sum_kernel).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// acc[s] += A[s] * b for s = 0..3, where A is the quadruple held by lanes 4*ABID .. 4*ABID+3 of the
+// caller's group of 2^CBSZ blocks of four lanes (the whole wave for CBSZ = 4).
+template <int CBSZ, int ABID>
+__device__ __forceinline__ void rank1_update(f32x4 &acc, float a_quads, float b)
+{
+    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a_quads, b, acc, CBSZ, ABID, 0);
+}
+
 template <int STREAMS, int T, bool DX>
-__global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const PairRecord *__restrict__ rec,
-                                                            const PairRecord *__restrict__ rec_d,
+__global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRecords rec,
                                                             const float *__restrict__ gy,
                                                             const float *__restrict__ cf,
                                                             const float *__restrict__ w_b,
@@ -259,6 +279,8 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
                                                             int n_jt, int blocks_per_chunk, int xcd_groups)
 {
     constexpr int LPS = 64 / STREAMS;
+    constexpr int RPW = LPS / 4;                    // records whose weights fit one register of a stream
+    constexpr int CBSZ = STREAMS == 1 ? 4 : (STREAMS == 2 ? 3 : 2);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane / LPS, q = lane % LPS, r16 = lane & 15;
     // Workgroups go to the 8 XCDs round-robin.  The XCDs form m = min(8, n_chunks) groups (m a power of
@@ -278,23 +300,24 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
     const int jc = jok ? j : 0;
     const int64_t b0 = (int64_t)c * S;
     const int n_c = (int)((B - b0) < S ? (B - b0) : S);
-    const PairRecord *list = rec + ((int64_t)c * g.n_in + i) * S;
-    const PairRecord *list_d = DX ? rec_d + ((int64_t)c * g.n_in + i) * S : nullptr;
+    const int64_t list = ((int64_t)c * g.n_in + i) * S;
     const float *gyp = gy + b0 * g.n_out + jc;
     const bool store_c = jok && part_c != nullptr;
     float *out = part_c + ((int64_t)c * g.n_in + i) * g.rows * g.n_out + jc;
     const float *cfi = DX ? cf + (int64_t)i * g.slab_rows * g.n_out + jc : nullptr;
     float *gxo = DX ? gx + (int64_t)jt * B * g.n_in + b0 * g.n_in + i : nullptr;
 
-    float a[kMaxK][T], hi[kMaxK][T], ab[T], abh[T], zero[T];
+    // a[r][s]: running sum of output j + r, window row cur + s; hi: the second level
+    f32x4 a[T], hi[T];
+    float ab[T], abh[T], zero[T];
 #pragma unroll
     for (int r = 0; r < T; ++r) {
         ab[r] = 0.0f; abh[r] = 0.0f; zero[r] = 0.0f;
-#pragma unroll
-        for (int s = 0; s < kMaxK; ++s) { a[s][r] = 0.0f; hi[s][r] = 0.0f; }
+        a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        hi[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
 
-    int cur = list[0].rt & 0xffff;           // first row of the window the accumulators stand on
+    int cur = rec.rt[list] & 0xffff;         // first row of the window the accumulators stand on
     if (store_c)
         for (int m = 0; m < cur; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
 
@@ -313,14 +336,35 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
         }
     }
 
+    // one batch of 16 records as the lanes hold it: row | sample and base value of record r16, the
+    // weight quadruples of the stream's 16 records spread over STREAMS registers (lane q of register u
+    // holds float number u * LPS + q of the batch's 64), the derivative record of r16
+    struct Batch {
+        int rt;
+        float base;
+        float wq[STREAMS];
+        float dw[kMaxK];
+        float dbase;
+    };
+    auto load_batch = [&](int bi) {
+        Batch t;
+        const int64_t at = list + (int64_t)bi * 16;
+        t.rt = rec.rt[at + r16];
+        t.base = rec.base[at + r16];
+#pragma unroll
+        for (int u = 0; u < STREAMS; ++u) t.wq[u] = rec.w4[at * 4 + u * LPS + q];
+        if constexpr (DX) {
+            const float4 d = *reinterpret_cast<const float4 *>(rec.dw4 + (at + r16) * 4);
+            t.dw[0] = d.x; t.dw[1] = d.y; t.dw[2] = d.z; t.dw[3] = d.w;
+            t.dbase = rec.dbase[at + r16];
+        }
+        return t;
+    };
+
     const int nb = (n_c + 15) / 16;
-    PairRecord mine = list[r16], mine_d;
-    if constexpr (DX) mine_d = list_d[r16];
+    Batch mine = load_batch(0);
     for (int bi = 0; bi < nb; ++bi) {
-        const int nxt = (bi + 1 < nb ? bi + 1 : bi) * 16 + r16;
-        const PairRecord upcoming = list[nxt];
-        PairRecord upcoming_d;
-        if constexpr (DX) upcoming_d = list_d[nxt];
+        const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
         const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
         float dot[16];
         auto half = [&](auto h) {
@@ -339,14 +383,13 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
                     if (store_c) {
                         float o[T];
 #pragma unroll
-                        for (int r = 0; r < T; ++r) o[r] = a[0][r] + hi[0][r];
+                        for (int r = 0; r < T; ++r) o[r] = a[r][0] + hi[r][0];
                         store_vec<T>(out + (int64_t)cur * g.n_out, o);
                     }
 #pragma unroll
                     for (int r = 0; r < T; ++r) {
-#pragma unroll
-                        for (int s = 0; s + 1 < kMaxK; ++s) { a[s][r] = a[s + 1][r]; hi[s][r] = hi[s + 1][r]; }
-                        a[kMaxK - 1][r] = 0.0f; hi[kMaxK - 1][r] = 0.0f;
+                        a[r] = f32x4{a[r][1], a[r][2], a[r][3], 0.0f};
+                        hi[r] = f32x4{hi[r][1], hi[r][2], hi[r][3], 0.0f};
                     }
                     ++cur;
                     if constexpr (DX) {
@@ -360,29 +403,19 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
                         for (int r = 0; r < T; ++r) cw[kMaxK - 1][r] *= jmask;
                     }
                 };
-                // (the compiler peels this loop; with the dL/dx state on top that costs more registers
-                // than it saves instructions)
-                if constexpr (DX) {
 #pragma clang loop unroll(disable)
-                    while (cur < row0) advance();
-                } else {
-                    while (cur < row0) advance();
-                }
-                const float w0 = row_bcast<R>(mine.w[0]), w1 = row_bcast<R>(mine.w[1]);
-                const float w2 = row_bcast<R>(mine.w[2]), w3 = row_bcast<R>(mine.w[3]);
+                while (cur < row0) advance();
                 const float bs = row_bcast<R>(mine.base);
 #pragma unroll
                 for (int r = 0; r < T; ++r) {
-                    a[0][r] = fmaf(w0, gr[N][r], a[0][r]);
-                    a[1][r] = fmaf(w1, gr[N][r], a[1][r]);
-                    a[2][r] = fmaf(w2, gr[N][r], a[2][r]);
-                    a[3][r] = fmaf(w3, gr[N][r], a[3][r]);
+                    rank1_update<CBSZ, R % RPW>(a[r], mine.wq[R / RPW], gr[N][r]);
                     ab[r] = fmaf(bs, gr[N][r], ab[r]);
+                    asm volatile("" : "+v"(ab[r]));     // keep the base term with its record (see below)
                 }
                 if constexpr (DX) {
-                    const float d0 = row_bcast<R>(mine_d.w[0]), d1 = row_bcast<R>(mine_d.w[1]);
-                    const float d2 = row_bcast<R>(mine_d.w[2]), d3 = row_bcast<R>(mine_d.w[3]);
-                    const float db = row_bcast<R>(mine_d.base);
+                    const float d0 = row_bcast<R>(mine.dw[0]), d1 = row_bcast<R>(mine.dw[1]);
+                    const float d2 = row_bcast<R>(mine.dw[2]), d3 = row_bcast<R>(mine.dw[3]);
+                    const float db = row_bcast<R>(mine.dbase);
                     float acc = 0.0f;
 #pragma unroll
                     for (int r = 0; r < T; ++r) {
@@ -411,13 +444,12 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
         if ((bi & 15) == 15) {
 #pragma unroll
             for (int r = 0; r < T; ++r) {
-#pragma unroll
-                for (int s = 0; s < kMaxK; ++s) { hi[s][r] += a[s][r]; a[s][r] = 0.0f; }
+                hi[r] += a[r];
+                a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
                 abh[r] += ab[r]; ab[r] = 0.0f;
             }
         }
         mine = upcoming;
-        if constexpr (DX) mine_d = upcoming_d;
     }
 
     if (!store_c) return;
@@ -425,7 +457,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, const 
     for (int s = 0; s < kMaxK; ++s) {
         float o[T];
 #pragma unroll
-        for (int r = 0; r < T; ++r) o[r] = a[s][r] + hi[s][r];
+        for (int r = 0; r < T; ++r) o[r] = a[r][s] + hi[r][s];
         store_vec<T>(out + (int64_t)(cur + s) * g.n_out, o);
     }
     for (int m = cur + kMaxK; m < g.rows; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
@@ -496,25 +528,26 @@ namespace {
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 }
 
-// transposed x | value records | derivative records | per-tile partial gx (layers wider than one tile)
+// transposed x | records (row|sample, base, weights, derivative base, derivative weights) |
+// per-tile partial gx (layers wider than one tile)
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
 {
-    const size_t recs = up256((size_t)p.n_chunks * n_in * p.S * sizeof(PairRecord));
+    const size_t n = (size_t)p.n_chunks * n_in * p.S;
     const size_t gxp = p.n_jt > 1 ? up256((size_t)p.n_jt * B * n_in * sizeof(float)) : 0;
-    return up256((size_t)B * n_in * sizeof(float)) + 2 * recs + gxp;
+    return up256((size_t)B * n_in * sizeof(float)) + 3 * up256(n * 4) + 2 * up256(n * 16) + gxp;
 }
 
 template <int STREAMS, int T>
-static void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const PairRecord *rec,
-                        const PairRecord *rec_d, const float *gy, const float *cf, const float *w_b, float *part_c,
-                        float *part_b, float *gx, int64_t B, const WalkPlan &p, int bpc, int m)
+static void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const WalkRecords &rec,
+                        const float *gy, const float *cf, const float *w_b, float *part_c, float *part_b, float *gx,
+                        int64_t B, const WalkPlan &p, int bpc, int m)
 {
     if (dx)
-        backward_walk_kernel<STREAMS, T, true><<<blocks, 256, 0, st>>>(g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx, B,
-                                                                      p.S, p.n_chunks, p.n_jt, bpc, m);
+        backward_walk_kernel<STREAMS, T, true><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
+                                                                      p.n_chunks, p.n_jt, bpc, m);
     else
-        backward_walk_kernel<STREAMS, T, false><<<blocks, 256, 0, st>>>(g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx, B,
-                                                                       p.S, p.n_chunks, p.n_jt, bpc, m);
+        backward_walk_kernel<STREAMS, T, false><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
+                                                                       p.n_chunks, p.n_jt, bpc, m);
 }
 
 // gx == nullptr: parameter gradients only.  part_c == nullptr: dL/dx only.  cf is the scale-folded
@@ -523,12 +556,17 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
                                 const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,
                                 float *part_b, int64_t B, hipStream_t st)
 {
-    const size_t recs = up256((size_t)p.n_chunks * g.n_in * p.S * sizeof(PairRecord));
-    float *xT = (float *)scratch;
-    PairRecord *rec = (PairRecord *)((char *)scratch + up256((size_t)B * g.n_in * sizeof(float)));
-    PairRecord *rec_d = (PairRecord *)((char *)rec + recs);
-    float *gx_part = (float *)((char *)rec_d + recs);
+    const size_t n = (size_t)p.n_chunks * g.n_in * p.S;
     const bool dx = gx != nullptr;
+    char *at = (char *)scratch;
+    float *xT = (float *)at;            at += up256((size_t)B * g.n_in * sizeof(float));
+    WalkRecords rec;
+    rec.rt = (int *)at;                 at += up256(n * 4);
+    rec.base = (float *)at;             at += up256(n * 4);
+    rec.w4 = (float *)at;               at += up256(n * 16);
+    rec.dbase = dx ? (float *)at : nullptr; at += up256(n * 4);
+    rec.dw4 = dx ? (float *)at : nullptr;   at += up256(n * 16);
+    float *gx_part = (float *)at;
     {
         dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
         prof::Timed tm("walk_transpose", st);
@@ -541,8 +579,7 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
         if (e != hipSuccess) return e;
         dim3 grid((unsigned)p.n_chunks, (unsigned)g.n_in);
         prof::Timed tm("walk_sort", st);
-        cell_sort_kernel<<<grid, kSortThreads, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec,
-                                                          dx ? rec_d : nullptr);
+        cell_sort_kernel<<<grid, kSortThreads, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec);
     }
     const int bpc = (p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
     int m = 1;
@@ -553,20 +590,20 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     {
         prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
         if (p.T == 4 && p.streams == 1)
-            walk_launch<1, 4>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<1, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
         else if (p.T == 4 && p.streams == 2)
-            walk_launch<2, 4>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<2, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
         else if (p.T == 4 && p.streams == 4)
-            walk_launch<4, 4>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<4, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
         else if (p.T == 1 && p.streams == 4)
-            walk_launch<4, 1>(dx, blocks, st, g, rec, rec_d, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<4, 1>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
         else
             return hipErrorInvalidValue;
     }
     if (dx && p.n_jt > 1) {
-        const int64_t n = B * g.n_in;
+        const int64_t nn = B * g.n_in;
         prof::Timed tm("walk_gx_sum", st);
-        gx_sum_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(gx_part, gx, n, p.n_jt);
+        gx_sum_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(gx_part, gx, nn, p.n_jt);
     }
     return hipGetLastError();
 }

@@ -152,6 +152,7 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "p"],
                     help="c2..c5: the benchmark configurations; p: the paper's 32->32, N=2^17 shape (see --grid)")
     ap.add_argument("--grid", type=int, default=64, help="grid size G of workload p")
+    ap.add_argument("--degree", type=int, default=3, help="spline degree k of workload p (1..3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="also time the dense basis x coefficient GEMM formulation of the forward pass")
@@ -175,7 +176,7 @@ def main():
         case = UkanCase(workloads.config5(), torch, binding)
     else:
         w = {"c2": workloads.config2, "c3": workloads.config3, "c4": workloads.config4,
-             "p": lambda: workloads.paper_shape(args.grid)}[args.workload]()
+             "p": lambda: workloads.paper_shape(args.grid, k=args.degree)}[args.workload]()
         case = KanCase(w, torch, binding)
 
     if args.copy_calibration:

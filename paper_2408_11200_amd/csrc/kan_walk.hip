@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                                                             const float *__restrict__ w_b,
                                                             float *__restrict__ part_c, float *__restrict__ part_b,
                                                             float *__restrict__ gx, int64_t B, int S, int n_chunks,
-                                                            int n_jt, int blocks_per_chunk, int xcd_groups)
+                                                            int n_jt, int blocks_per_chunk, int xcd_groups, int prezeroed)
 {
     constexpr int LPS = 64 / STREAMS;
     constexpr int RPW = LPS / 4;                    // records whose weights fit one register of a stream
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     }
 
     int cur = rec.rt[list] & 0xffff;         // first row of the window the accumulators stand on
-    if (store_c)
+    if (store_c && !prezeroed)
         for (int m = 0; m < cur; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
 
     // dL/dx: table rows cur .. cur+K-1 and the w_b row, zero in lanes past the last output
@@ -403,6 +403,35 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                         for (int r = 0; r < T; ++r) cw[kMaxK - 1][r] *= jmask;
                     }
                 };
+                if (row0 - cur >= kMaxK) {
+                    // the window jumps clear of its old position: write it out whole and start afresh
+                    // (rows in between are zero: stored here, or already zero when the slab was pre-zeroed)
+                    if (store_c) {
+#pragma unroll
+                        for (int s = 0; s < kMaxK; ++s) {
+                            float o[T];
+#pragma unroll
+                            for (int r = 0; r < T; ++r) o[r] = a[r][s] + hi[r][s];
+                            store_vec<T>(out + (int64_t)(cur + s) * g.n_out, o);
+                        }
+                        if (!prezeroed)
+                            for (int m = cur + kMaxK; m < row0; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
+                    }
+#pragma unroll
+                    for (int r = 0; r < T; ++r) {
+                        a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                        hi[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                    }
+                    cur = row0;
+                    if constexpr (DX) {
+#pragma unroll
+                        for (int s = 0; s < kMaxK; ++s) {
+                            load_vec<T>(cfi + (int64_t)(cur + s) * g.n_out, cw[s]);
+#pragma unroll
+                            for (int r = 0; r < T; ++r) cw[s][r] *= jmask;
+                        }
+                    }
+                }
 #pragma clang loop unroll(disable)
                 while (cur < row0) advance();
                 const float bs = row_bcast<R>(mine.base);
@@ -460,12 +489,24 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         for (int r = 0; r < T; ++r) o[r] = a[r][s] + hi[r][s];
         store_vec<T>(out + (int64_t)(cur + s) * g.n_out, o);
     }
-    for (int m = cur + kMaxK; m < g.rows; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
+    if (!prezeroed)
+        for (int m = cur + kMaxK; m < g.rows; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
     if (part_b) {
         float o[T];
 #pragma unroll
         for (int r = 0; r < T; ++r) o[r] = ab[r] + abh[r];
         store_vec<T>(part_b + ((int64_t)c * g.n_in + i) * g.n_out + jc, o);
+    }
+}
+
+// plain zero fill (a kernel rather than a memset so that the call sequence can be captured in a graph)
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n)
+{
+    const int64_t at = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (at + 3 < n) {
+        *reinterpret_cast<float4 *>(p + at) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    } else {
+        for (int64_t e = at; e < n; ++e) p[e] = 0.0f;
     }
 }
 
@@ -540,14 +581,14 @@ size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
 template <int STREAMS, int T>
 static void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const WalkRecords &rec,
                         const float *gy, const float *cf, const float *w_b, float *part_c, float *part_b, float *gx,
-                        int64_t B, const WalkPlan &p, int bpc, int m)
+                        int64_t B, const WalkPlan &p, int bpc, int m, int prezeroed)
 {
     if (dx)
         backward_walk_kernel<STREAMS, T, true><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
-                                                                      p.n_chunks, p.n_jt, bpc, m);
+                                                                      p.n_chunks, p.n_jt, bpc, m, prezeroed);
     else
         backward_walk_kernel<STREAMS, T, false><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
-                                                                       p.n_chunks, p.n_jt, bpc, m);
+                                                                       p.n_chunks, p.n_jt, bpc, m, prezeroed);
 }
 
 // gx == nullptr: parameter gradients only.  part_c == nullptr: dL/dx only.  cf is the scale-folded
@@ -587,16 +628,25 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
     const unsigned blocks = (unsigned)(8 * bpc_sub * ((p.n_chunks + m - 1) / m));
     float *gx_out = dx ? (p.n_jt > 1 ? gx_part : gx) : nullptr;
+    // Sparse regime (far more rows than a chunk has samples): most rows of a chunk's partial slab
+    // receive nothing.  The slab is zeroed with a streaming fill and the walk skips the gaps instead of
+    // stepping through them row by row.
+    const int prezeroed = (part_c != nullptr && g.rows > 2 * p.S) ? 1 : 0;
+    if (prezeroed) {
+        const int64_t n4 = (int64_t)p.n_chunks * g.n_in * g.rows * g.n_out;
+        prof::Timed tm("walk_zero_fill", st);
+        fill_zero_kernel<<<(unsigned)((n4 + 1023) / 1024), 256, 0, st>>>(part_c, n4);
+    }
     {
         prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
         if (p.T == 4 && p.streams == 1)
-            walk_launch<1, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<1, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
         else if (p.T == 4 && p.streams == 2)
-            walk_launch<2, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<2, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
         else if (p.T == 4 && p.streams == 4)
-            walk_launch<4, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<4, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
         else if (p.T == 1 && p.streams == 4)
-            walk_launch<4, 1>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m);
+            walk_launch<4, 1>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
         else
             return hipErrorInvalidValue;
     }

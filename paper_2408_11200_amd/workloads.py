@@ -162,12 +162,12 @@ def config5(seed=1005, B=32768, widths=(128, 256, 256, 1)):
     return Workload("C5 UKAN %s h0.25 k3 B%d" % (list(widths), B), B, specs, x, params, gy)
 
 
-def paper_shape(G, seed=1100, B=1 << 17):
+def paper_shape(G, seed=1100, B=1 << 17, k=3):
     """The paper's own benchmark shape (Table 2): 32->32, k=3, N=2^17, x uniform inside the grid."""
     rng = np.random.default_rng(seed + G)
-    spec = KanLayerSpec(32, 32, G, 3, -1.0, 1.0)
+    spec = KanLayerSpec(32, 32, G, k, -1.0, 1.0)
     x = _f32(rng.uniform(-1.0, 1.0, size=(B, 32)))
     x = np.minimum(x, np.float32(np.nextafter(np.float32(1.0), np.float32(0.0))))
     p = kan_params(rng, spec, 0.1, w_s_std=1.0 / np.sqrt(32), w_b_std=1.0 / np.sqrt(32))
     gy = _f32(rng.standard_normal((B, 32)))
-    return Workload("P KAN 32->32 G%d k3 B%d" % (G, B), B, [spec], x, [p], gy)
+    return Workload("P KAN 32->32 G%d k%d B%d" % (G, k, B), B, [spec], x, [p], gy)

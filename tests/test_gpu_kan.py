@@ -71,6 +71,9 @@ SWEEP = [
     (2100, 3, 132, 40, 2, 0.2),        # one stream per wave with a ragged output tile
     (900, 6, 96, 7, 3, 0.3),           # two streams per wave
     (300, 9, 12, 30, 3, 0.1),          # narrow layer, one output per lane
+    (700, 5, 32, 3000, 3, 0.1),        # far more rows than samples: pre-zeroed partial slabs, gap jumps
+    (1500, 3, 256, 2500, 2, 0.05),     # the same with one stream per wave
+    (64, 2, 8, 70000, 3, 0.1),         # more rows than the sorted path indexes: generic kernels
 ]
 
 

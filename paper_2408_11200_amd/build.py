@@ -10,6 +10,9 @@ LIB_PATH = os.path.join(HERE, "libkan_hip.so")
 # packed fp32 instructions are switched off for every translation unit
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               # matrix-core accumulators in ordinary VGPRs: the walk kernel reads and clears single
+               # accumulator rows between MFMAs, which through AGPRs costs a copy of all of them per record
+               "-mllvm", "-amdgpu-mfma-vgpr-form=1",
                "-Wno-unused-command-line-argument"]
 
 

@@ -67,8 +67,8 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     if (bp.walk) {
         bp.cp.n_chunks = bp.wp.n_chunks;
         bp.cp.chunk_len = bp.wp.S;
-        bp.rec_bytes = align_up(walk_scratch_bytes(bp.wp, B, g.n_in));
-        bp.b_slices_per_chunk = 1;
+        bp.rec_bytes = align_up(walk_scratch_bytes(bp.wp, B, g.n_in, g.n_out));
+        bp.b_slices_per_chunk = bp.wp.n_seg;
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
         bp.rec_bytes = 0;

@@ -72,12 +72,13 @@ struct WalkPlan {
     int ok;
     int S, sbits;        // samples per chunk (power of two) and its log2
     int n_chunks;
+    int n_seg;           // segments each sorted list is cut into (one stream each), a power of two
     int streams, T;      // streams per wave, outputs per lane
     int n_jt;            // output tiles of (64 / streams) * T outputs
     int row_bits;        // bits of the largest window row (sort key width)
 };
 WalkPlan plan_walk(const SplineGeom &g, int64_t B);
-size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in);
+size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out);
 hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,
                                 const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,
                                 float *part_b, int64_t B, hipStream_t st);

@@ -38,8 +38,6 @@ namespace kan {
 
 namespace {
 
-constexpr int kSortThreads = 256;
-
 // ---- 1. transpose --------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ x, float *__restrict__ xT,
                                                         int64_t B, int n_in)
@@ -56,20 +54,22 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
 }
 
 // ---- 2. sort + records ---------------------------------------------------------------------
-// grid (n_chunks, n_in), 256 threads.  key = window row << sbits | sample index in the chunk
+// grid (n_chunks, n_in), NW waves.  key = window row << sbits | sample index in the chunk
 // (sbits = log2 S): keys are distinct, and sorting them by the row digits with a stable counting
 // sort keeps samples of equal row in batch order, which fixes the summation order downstream.
-// Each wave owns a contiguous quarter of the sequence; digit counts are taken per wave, the
+// Each wave owns a contiguous share of the sequence; digit counts are taken per wave, the
 // (digit, wave) prefix gives every wave its first slot per digit, and the wave then places its
 // keys batch by batch (rank inside a batch from ballots), so nothing depends on timing.
 // Entries past the end of the batch get the largest row and end up behind every real record.
-__global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, const float *__restrict__ xT, int64_t B,
-                                                                 int S, int sbits, int row_bits, WalkRecords rec)
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void cell_sort_kernel(SplineGeom g, const float *__restrict__ xT, int64_t B,
+                                                            int S, int sbits, int row_bits, WalkRecords rec)
 {
+    constexpr int kSortThreads = 64 * NW;
     extern __shared__ unsigned lds_u[];
     unsigned *src = lds_u, *dst = lds_u + S;
     float *xs = reinterpret_cast<float *>(lds_u + 2 * S);
-    __shared__ unsigned slot[4][256];
+    __shared__ unsigned slot[NW][256];
     __shared__ unsigned wave_tot[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = blockIdx.x, i = blockIdx.y;
@@ -90,31 +90,38 @@ __global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, c
     }
     __syncthreads();
 
-    const int per_wave = S / 4;
+    const int per_wave = S / NW;                    // a multiple of 64
     const int n_pass = (row_bits + 7) / 8;
     const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
     for (int pass = 0; pass < n_pass; ++pass) {
         const int shift = sbits + 8 * pass;
         const int nbits = row_bits - 8 * pass < 8 ? row_bits - 8 * pass : 8;
-        for (int d = tid; d < 4 * 256; d += kSortThreads) (&slot[0][0])[d] = 0u;
+        for (int d = tid; d < NW * 256; d += kSortThreads) (&slot[0][0])[d] = 0u;
         __syncthreads();
         for (int e = wave * per_wave + lane; e < (wave + 1) * per_wave; e += 64)
             atomicAdd(&slot[wave][(src[e] >> shift) & 255u], 1u);
         __syncthreads();
-        {
-            const unsigned c0 = slot[0][tid], c1 = slot[1][tid], c2 = slot[2][tid], c3 = slot[3][tid];
-            const unsigned tot = c0 + c1 + c2 + c3;
-            unsigned inc = tot;
+        // first slot of every (digit, wave): exclusive prefix over digits, then over waves; done by
+        // the first 256 threads (one digit each)
+        unsigned tot = 0, inc = 0;
+        if (tid < 256) {
+            for (int w2 = 0; w2 < NW; ++w2) tot += slot[w2][tid];
+            inc = tot;
             for (int o = 1; o < 64; o <<= 1) {
                 const unsigned v = __shfl_up(inc, o, 64);
                 if (lane >= o) inc += v;
             }
             if (lane == 63) wave_tot[wave] = inc;
-            __syncthreads();
-            unsigned before = 0;
-            for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
-            const unsigned ex = before + inc - tot;
-            slot[0][tid] = ex; slot[1][tid] = ex + c0; slot[2][tid] = ex + c0 + c1; slot[3][tid] = ex + c0 + c1 + c2;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            unsigned at = inc - tot;
+            for (int w2 = 0; w2 < wave; ++w2) at += wave_tot[w2];
+            for (int w2 = 0; w2 < NW; ++w2) {
+                const unsigned cnt = slot[w2][tid];
+                slot[w2][tid] = at;
+                at += cnt;
+            }
         }
         __syncthreads();
         for (int e0 = wave * per_wave; e0 < (wave + 1) * per_wave; e0 += 64) {
@@ -151,12 +158,26 @@ __global__ __launch_bounds__(kSortThreads) void cell_sort_kernel(SplineGeom g, c
             for (int s = 0; s < kMaxK; ++s) { w[s] = 0.0f; dw[s] = 0.0f; }
             base = 0.0f; dbase = 0.0f;
         }
+        // The consumer keeps its K window rows in a ring indexed by (row mod K): store the weight of
+        // window row row0 + s in position (row0 + s) mod K, so that it needs no shifting there.
+        float wr[kMaxK], dwr[kMaxK];
+#pragma unroll
+        for (int q = 0; q < kMaxK; ++q) {
+            float v = 0.0f, dv = 0.0f;
+#pragma unroll
+            for (int s = 0; s < kMaxK; ++s) {
+                const bool hit = ((row0 + s) & (kMaxK - 1)) == q;
+                v = hit ? w[s] : v;
+                dv = hit ? dw[s] : dv;
+            }
+            wr[q] = v; dwr[q] = dv;
+        }
         rec.rt[list + p] = row0 | ((live ? e : 0) << 16);
         rec.base[list + p] = base;
-        *reinterpret_cast<float4 *>(rec.w4 + (list + p) * 4) = make_float4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<float4 *>(rec.w4 + (list + p) * 4) = make_float4(wr[0], wr[1], wr[2], wr[3]);
         if (rec.dw4) {
             rec.dbase[list + p] = dbase;
-            *reinterpret_cast<float4 *>(rec.dw4 + (list + p) * 4) = make_float4(dw[0], dw[1], dw[2], dw[3]);
+            *reinterpret_cast<float4 *>(rec.dw4 + (list + p) * 4) = make_float4(dwr[0], dwr[1], dwr[2], dwr[3]);
         }
     }
 }
@@ -276,7 +297,8 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                                                             const float *__restrict__ w_b,
                                                             float *__restrict__ part_c, float *__restrict__ part_b,
                                                             float *__restrict__ gx, int64_t B, int S, int n_chunks,
-                                                            int n_jt, int blocks_per_chunk, int xcd_groups, int prezeroed)
+                                                            int n_jt, int blocks_per_chunk, int xcd_groups, int prezeroed, int n_seg,
+                                                            float *__restrict__ carry)
 {
     constexpr int LPS = 64 / STREAMS;
     constexpr int RPW = LPS / 4;                    // records whose weights fit one register of a stream
@@ -292,15 +314,21 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     const int c = grp + xcd_groups * (slot / bpc_sub);
     const int blk = (slot % bpc_sub) * n_sub + sub_x;
     const int ws = (blk * 4 + wave) * STREAMS + sub;
-    if (c >= n_chunks || blk >= blocks_per_chunk || ws >= n_jt * g.n_in) return;
+    if (c >= n_chunks || blk >= blocks_per_chunk || ws >= n_seg * n_jt * g.n_in) return;
     const int i = ws % g.n_in;
-    const int jt = ws / g.n_in;
+    const int jt = (ws / g.n_in) % n_jt;
+    const int seg = ws / (g.n_in * n_jt);
+    const int seg_len = S / n_seg;                  // a multiple of 16
     const int j = (jt * LPS + q) * T;
     const bool jok = j < g.n_out;
     const int jc = jok ? j : 0;
     const int64_t b0 = (int64_t)c * S;
     const int n_c = (int)((B - b0) < S ? (B - b0) : S);
-    const int64_t list = ((int64_t)c * g.n_in + i) * S;
+    const int64_t list0 = ((int64_t)c * g.n_in + i) * S;
+    const int64_t list = list0 + (int64_t)seg * seg_len;        // this segment's records
+    // The segment owns the table rows from its first record's row up to the next segment's first
+    // row; what its window holds beyond that at the end goes to the next segment's carry rows.
+    const int r_next = seg + 1 < n_seg ? (rec.rt[list + seg_len] & 0xffff) : g.rows;
     const float *gyp = gy + b0 * g.n_out + jc;
     const bool store_c = jok && part_c != nullptr;
     float *out = part_c + ((int64_t)c * g.n_in + i) * g.rows * g.n_out + jc;
@@ -318,7 +346,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     }
 
     int cur = rec.rt[list] & 0xffff;         // first row of the window the accumulators stand on
-    if (store_c && !prezeroed)
+    if (store_c && !prezeroed && seg == 0)
         for (int m = 0; m < cur; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
 
     // dL/dx: table rows cur .. cur+K-1 and the w_b row, zero in lanes past the last output
@@ -328,13 +356,50 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
 #pragma unroll
         for (int r = 0; r < T; ++r) wb[r] = 0.0f;
         if (jok && w_b != nullptr && g.base_act != 0) load_vec<T>(w_b + (int64_t)i * g.n_out + j, wb);
-#pragma unroll
-        for (int s = 0; s < kMaxK; ++s) {
-            load_vec<T>(cfi + (int64_t)(cur + s) * g.n_out, cw[s]);
-#pragma unroll
-            for (int r = 0; r < T; ++r) cw[s][r] *= jmask;
-        }
     }
+
+    // The window rows live in a ring: row m of the table is component m mod K of a[r] / hi[r] (and of
+    // cw for dL/dx); the records carry their weights in the same arrangement.  retire() completes the
+    // first row of the window: stores it (store == false: returns it in `gone` only), clears its
+    // component and, for dL/dx, loads the table row that enters the window in its place.
+    float gone[T];
+    auto retire_slot = [&](auto sl, bool store, bool enter_next) {
+        constexpr int SL = decltype(sl)::value;
+#pragma unroll
+        for (int r = 0; r < T; ++r) {
+            gone[r] = a[r][SL] + hi[r][SL];
+            a[r][SL] = 0.0f;
+            hi[r][SL] = 0.0f;
+        }
+        if (store && store_c) store_vec<T>(out + (int64_t)cur * g.n_out, gone);
+        if (DX && enter_next) {
+            const int enter = cur + kMaxK < g.rows ? cur + kMaxK : g.rows - 1;     // clamped: unused past the end
+            load_vec<T>(cfi + (int64_t)enter * g.n_out, cw[SL]);
+#pragma unroll
+            for (int r = 0; r < T; ++r) cw[SL][r] *= jmask;
+        }
+    };
+    auto retire = [&](bool store, bool enter_next) {
+        switch (cur & (kMaxK - 1)) {
+        case 0: retire_slot(std::integral_constant<int, 0>{}, store, enter_next); break;
+        case 1: retire_slot(std::integral_constant<int, 1>{}, store, enter_next); break;
+        case 2: retire_slot(std::integral_constant<int, 2>{}, store, enter_next); break;
+        default: retire_slot(std::integral_constant<int, 3>{}, store, enter_next); break;
+        }
+        ++cur;
+    };
+    auto reload_table_rows = [&]() {
+        if constexpr (DX) {
+#pragma unroll
+            for (int s = 0; s < kMaxK; ++s) {
+                // component s holds the row of the window that is congruent to s
+                const int row = cur + ((s - cur) & (kMaxK - 1));
+                load_vec<T>(cfi + (int64_t)row * g.n_out, cw[s]);
+#pragma unroll
+                for (int r = 0; r < T; ++r) cw[s][r] *= jmask;
+            }
+        }
+    };
 
     // one batch of 16 records as the lanes hold it: row | sample and base value of record r16, the
     // weight quadruples of the stream's 16 records spread over STREAMS registers (lane q of register u
@@ -361,7 +426,11 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         return t;
     };
 
-    const int nb = (n_c + 15) / 16;
+    reload_table_rows();
+
+    // every record of the segment is walked, the padding behind the last sample of a ragged chunk
+    // included (zero weights, sorted last)
+    const int nb = seg_len / 16;
     Batch mine = load_batch(0);
     for (int bi = 0; bi < nb; ++bi) {
         const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
@@ -379,61 +448,19 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                 constexpr int N = decltype(n)::value;
                 constexpr int R = H * 8 + N;
                 const int row0 = row_bcast<R>(rowv);
-                auto advance = [&]() {          // the window moves on: its first row is complete
-                    if (store_c) {
-                        float o[T];
-#pragma unroll
-                        for (int r = 0; r < T; ++r) o[r] = a[r][0] + hi[r][0];
-                        store_vec<T>(out + (int64_t)cur * g.n_out, o);
-                    }
-#pragma unroll
-                    for (int r = 0; r < T; ++r) {
-                        a[r] = f32x4{a[r][1], a[r][2], a[r][3], 0.0f};
-                        hi[r] = f32x4{hi[r][1], hi[r][2], hi[r][3], 0.0f};
-                    }
-                    ++cur;
-                    if constexpr (DX) {
-#pragma unroll
-                        for (int r = 0; r < T; ++r) {
-#pragma unroll
-                            for (int s = 0; s + 1 < kMaxK; ++s) cw[s][r] = cw[s + 1][r];
-                        }
-                        load_vec<T>(cfi + (int64_t)(cur + kMaxK - 1) * g.n_out, cw[kMaxK - 1]);
-#pragma unroll
-                        for (int r = 0; r < T; ++r) cw[kMaxK - 1][r] *= jmask;
-                    }
-                };
                 if (row0 - cur >= kMaxK) {
                     // the window jumps clear of its old position: write it out whole and start afresh
                     // (rows in between are zero: stored here, or already zero when the slab was pre-zeroed)
-                    if (store_c) {
+                    const int from = cur + kMaxK;
 #pragma unroll
-                        for (int s = 0; s < kMaxK; ++s) {
-                            float o[T];
-#pragma unroll
-                            for (int r = 0; r < T; ++r) o[r] = a[r][s] + hi[r][s];
-                            store_vec<T>(out + (int64_t)(cur + s) * g.n_out, o);
-                        }
-                        if (!prezeroed)
-                            for (int m = cur + kMaxK; m < row0; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
-                    }
-#pragma unroll
-                    for (int r = 0; r < T; ++r) {
-                        a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                        hi[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                    }
+                    for (int s = 0; s < kMaxK; ++s) retire(true, false);
+                    if (store_c && !prezeroed)
+                        for (int m = from; m < row0; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
                     cur = row0;
-                    if constexpr (DX) {
-#pragma unroll
-                        for (int s = 0; s < kMaxK; ++s) {
-                            load_vec<T>(cfi + (int64_t)(cur + s) * g.n_out, cw[s]);
-#pragma unroll
-                            for (int r = 0; r < T; ++r) cw[s][r] *= jmask;
-                        }
-                    }
+                    if constexpr (DX) reload_table_rows();
                 }
 #pragma clang loop unroll(disable)
-                while (cur < row0) advance();
+                while (cur < row0) retire(true, true);
                 const float bs = row_bcast<R>(mine.base);
 #pragma unroll
                 for (int r = 0; r < T; ++r) {
@@ -468,7 +495,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
             const float total = reduce_levels<LPS / 2, 16>(dot, lane);
             const int qn = quantity_of<LPS>(lane);
             const int t = __shfl(tv, (lane & ~15) | qn, 64);
-            if ((lane % (LPS / 16)) == 0 && bi * 16 + qn < n_c) gxo[(int64_t)t * g.n_in] = total;
+            if ((lane % (LPS / 16)) == 0 && seg * seg_len + bi * 16 + qn < n_c) gxo[(int64_t)t * g.n_in] = total;
         }
         if ((bi & 15) == 15) {
 #pragma unroll
@@ -482,20 +509,45 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     }
 
     if (!store_c) return;
+    // what the window still holds: rows below r_next belong to this segment, the others to the next
+    // segment's carry rows (carry row s2 stands for table row r_next + s2)
+    float *cr = carry + ((((int64_t)c * g.n_in + i) * n_seg + seg + 1) * kMaxK) * g.n_out + jc;
+    const int last = cur + kMaxK;            // one past the window
 #pragma unroll
     for (int s = 0; s < kMaxK; ++s) {
-        float o[T];
-#pragma unroll
-        for (int r = 0; r < T; ++r) o[r] = a[r][s] + hi[r][s];
-        store_vec<T>(out + (int64_t)(cur + s) * g.n_out, o);
+        const int row = cur;
+        retire(row < r_next, false);
+        if (row >= r_next && seg + 1 < n_seg) store_vec<T>(cr + (int64_t)(row - r_next) * g.n_out, gone);
     }
+    if (seg + 1 < n_seg)
+        for (int s2 = (last > r_next ? last - r_next : 0); s2 < kMaxK; ++s2) store_vec<T>(cr + (int64_t)s2 * g.n_out, zero);
     if (!prezeroed)
-        for (int m = cur + kMaxK; m < g.rows; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
+        for (int m = last; m < r_next; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
     if (part_b) {
         float o[T];
 #pragma unroll
         for (int r = 0; r < T; ++r) o[r] = ab[r] + abh[r];
-        store_vec<T>(part_b + ((int64_t)c * g.n_in + i) * g.n_out + jc, o);
+        store_vec<T>(part_b + (((int64_t)c * n_seg + seg) * g.n_in + i) * g.n_out + jc, o);
+    }
+}
+
+// Adds the carry rows of segments 1 .. n_seg-1 to the partial slabs, in segment order.  One thread
+// per (chunk, input, output).
+__global__ __launch_bounds__(256) void walk_carry_kernel(SplineGeom g, const int *__restrict__ rt,
+                                                         const float *__restrict__ carry, float *__restrict__ part_c,
+                                                         int S, int n_chunks, int n_seg)
+{
+    const int64_t at = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (at >= (int64_t)n_chunks * g.n_in * g.n_out) return;
+    const int j = (int)(at % g.n_out);
+    const int64_t ci = at / g.n_out;               // chunk * n_in + input
+    const int seg_len = S / n_seg;
+    float *slab = part_c + ci * g.rows * g.n_out + j;
+    for (int k = 1; k < n_seg; ++k) {
+        const int rf = rt[ci * S + (int64_t)k * seg_len] & 0xffff;
+        const float *cr = carry + ((ci * n_seg + k) * kMaxK) * g.n_out + j;
+        for (int s = 0; s < kMaxK; ++s)
+            if (rf + s < g.rows) slab[(int64_t)(rf + s) * g.n_out] += cr[(int64_t)s * g.n_out];
     }
 }
 
@@ -542,22 +594,25 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
     }
     const int tile = (64 / p.streams) * p.T;
     p.n_jt = (g.n_out + tile - 1) / tile;
-    // chunk length: a power of two between 256 and 8192 samples, the smallest of
+    // chunk length: a power of two between 256 and 8192 samples, the smaller of
     //   - what keeps the gy rows of one chunk inside an XCD's L2 (about 2 MiB of it),
-    //   - what gives the chip about 2048 waves,
     //   - an eighth of the batch (one chunk per XCD at least),
-    // then raised until the partial sums fit 2 GiB.
+    // then raised until the partial sums fit 2 GiB.  Few, long chunks keep the partial sums small;
+    // the parallelism comes from cutting each sorted list into segments (below).
     auto pow2_floor = [](int64_t v) { int64_t q = 256; while (q * 2 <= v && q < 8192) q *= 2; return (int)q; };
     int S = pow2_floor((2ll << 20) / ((int64_t)g.n_out * 4));
-    const int s_par = pow2_floor(B * p.n_jt * g.n_in / ((int64_t)p.streams * 2048));
     const int s_b8 = pow2_floor(B / 8);
-    S = S < s_par ? S : s_par;
     S = S < s_b8 ? S : s_b8;
     const int64_t slab = (int64_t)g.n_in * g.rows * g.n_out * (int64_t)sizeof(float);
     while (S < 8192 && ((B + S - 1) / S) * slab > (2ll << 30)) S *= 2;
     p.S = S;
     p.sbits = log2_exact(S);
     p.n_chunks = (int)((B + S - 1) / S);
+    // segments per list: enough for about 2048 waves, at least 64 records each
+    p.n_seg = 1;
+    while (S / (p.n_seg * 2) >= 64 &&
+           (int64_t)p.n_chunks * p.n_seg * p.n_jt * g.n_in < (int64_t)2048 * p.streams)
+        p.n_seg *= 2;
     int bits = 0;
     while ((1 << bits) < g.rows - kMaxK + 1) ++bits;
     p.row_bits = bits < 1 ? 1 : bits;
@@ -570,25 +625,33 @@ size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 }
 
 // transposed x | records (row|sample, base, weights, derivative base, derivative weights) |
-// per-tile partial gx (layers wider than one tile)
-size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in)
+// per-tile partial gx (layers wider than one tile) | carry rows of the list segments
+static size_t walk_carry_bytes(const WalkPlan &p, int n_in, int n_out)
+{
+    return up256((size_t)p.n_chunks * n_in * (p.n_seg + 1) * kMaxK * n_out * sizeof(float));
+}
+
+size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out)
 {
     const size_t n = (size_t)p.n_chunks * n_in * p.S;
     const size_t gxp = p.n_jt > 1 ? up256((size_t)p.n_jt * B * n_in * sizeof(float)) : 0;
-    return up256((size_t)B * n_in * sizeof(float)) + 3 * up256(n * 4) + 2 * up256(n * 16) + gxp;
+    return up256((size_t)B * n_in * sizeof(float)) + 3 * up256(n * 4) + 2 * up256(n * 16) + gxp +
+           walk_carry_bytes(p, n_in, n_out);
 }
 
 template <int STREAMS, int T>
 static void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const WalkRecords &rec,
                         const float *gy, const float *cf, const float *w_b, float *part_c, float *part_b, float *gx,
-                        int64_t B, const WalkPlan &p, int bpc, int m, int prezeroed)
+                        int64_t B, const WalkPlan &p, int bpc, int m, int prezeroed, float *carry)
 {
     if (dx)
         backward_walk_kernel<STREAMS, T, true><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
-                                                                      p.n_chunks, p.n_jt, bpc, m, prezeroed);
+                                                                      p.n_chunks, p.n_jt, bpc, m, prezeroed, p.n_seg,
+                                                                      carry);
     else
         backward_walk_kernel<STREAMS, T, false><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
-                                                                       p.n_chunks, p.n_jt, bpc, m, prezeroed);
+                                                                       p.n_chunks, p.n_jt, bpc, m, prezeroed, p.n_seg,
+                                                                       carry);
 }
 
 // gx == nullptr: parameter gradients only.  part_c == nullptr: dL/dx only.  cf is the scale-folded
@@ -607,7 +670,8 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     rec.w4 = (float *)at;               at += up256(n * 16);
     rec.dbase = dx ? (float *)at : nullptr; at += up256(n * 4);
     rec.dw4 = dx ? (float *)at : nullptr;   at += up256(n * 16);
-    float *gx_part = (float *)at;
+    float *gx_part = (float *)at;       at += p.n_jt > 1 ? up256((size_t)p.n_jt * B * g.n_in * sizeof(float)) : 0;
+    float *carry = (float *)at;
     {
         dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
         prof::Timed tm("walk_transpose", st);
@@ -615,14 +679,16 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     }
     {
         const size_t lds = (size_t)p.S * 12;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(cell_sort_kernel),
+        // long chunks: 16 waves per sort (one workgroup per CU fits anyway), short ones 4
+        auto kern = p.S >= 4096 ? cell_sort_kernel<16> : cell_sort_kernel<4>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         dim3 grid((unsigned)p.n_chunks, (unsigned)g.n_in);
         prof::Timed tm("walk_sort", st);
-        cell_sort_kernel<<<grid, kSortThreads, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec);
+        kern<<<grid, p.S >= 4096 ? 1024 : 256, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec);
     }
-    const int bpc = (p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
+    const int bpc = (p.n_seg * p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
     int m = 1;
     while (m * 2 <= 8 && m * 2 <= p.n_chunks) m *= 2;
     const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
@@ -640,15 +706,21 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     {
         prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
         if (p.T == 4 && p.streams == 1)
-            walk_launch<1, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
+            walk_launch<1, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
         else if (p.T == 4 && p.streams == 2)
-            walk_launch<2, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
+            walk_launch<2, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
         else if (p.T == 4 && p.streams == 4)
-            walk_launch<4, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
+            walk_launch<4, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
         else if (p.T == 1 && p.streams == 4)
-            walk_launch<4, 1>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed);
+            walk_launch<4, 1>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
         else
             return hipErrorInvalidValue;
+    }
+    if (part_c != nullptr && p.n_seg > 1) {
+        const int64_t nn = (int64_t)p.n_chunks * g.n_in * g.n_out;
+        prof::Timed tm("walk_carry", st);
+        walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.S, p.n_chunks,
+                                                                       p.n_seg);
     }
     if (dx && p.n_jt > 1) {
         const int64_t nn = B * g.n_in;

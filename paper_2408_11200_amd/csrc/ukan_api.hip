@@ -33,11 +33,18 @@ WalkPlan walk_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
     return plan_walk(g, B);
 }
 
+// base-term partial slices each chunk writes
+int b_slices_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
+{
+    const WalkPlan wp = walk_for(d, B, max_groups);
+    return wp.ok ? wp.n_seg : dparam_generic_row_blocks(max_groups * (d->k + 1));
+}
+
 // scratch of the walk's pre-pass (transposed x + sorted records)
 size_t record_bytes_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
     const WalkPlan wp = walk_for(d, B, max_groups);
-    return wp.ok ? walk_scratch_bytes(wp, B, d->n_in) : 0;
+    return wp.ok ? walk_scratch_bytes(wp, B, d->n_in, d->n_out) : 0;
 }
 
 ChunkPlan chunks_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
@@ -61,7 +68,8 @@ struct Layout {
 
 int split_slices(int64_t rows) { int64_t s = (rows + 511) / 512; return (int)(s < 1 ? 1 : (s > 64 ? 64 : s)); }
 
-Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunks, size_t rec_bytes, int pass)
+Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunks, size_t rec_bytes, int b_slices,
+                   int pass)
 {
     const size_t K = (size_t)d->k + 1, n_in = (size_t)d->n_in, n_out = (size_t)d->n_out;
     const size_t rows = n_in * (size_t)n_g, n_o = K * n_out, dz = (size_t)d->d_feat + d->d_pe, dh = (size_t)d->d_hidden;
@@ -80,7 +88,7 @@ Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunk
         L.raw = take(table);
         L.rec = take(rec_bytes);
         L.part_c = take((size_t)n_chunks * table);
-        L.part_b = take((size_t)n_chunks * dparam_generic_row_blocks((int)((size_t)n_g * K)) * n_in * n_out * 4);   // >= the slice count of the other kernels
+        L.part_b = take((size_t)n_chunks * b_slices * n_in * n_out * 4);
         L.gout = take(table);
         L.gpre = take(rows * dh * 4);
         size_t s1 = (size_t)split_slices((int64_t)rows) * dh * n_o * 4;      // gW2 partials
@@ -107,7 +115,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     const int K = d->k + 1;
     const float inv_h = 1.0f / d->h;
     out->cp = chunks_for(d, B, max_groups);
-    Layout L0 = make_layout(d, B, max_groups, out->cp.n_chunks, record_bytes_for(d, B, max_groups), pass);     // meta offsets do not depend on n_g
+    Layout L0 = make_layout(d, B, max_groups, out->cp.n_chunks, record_bytes_for(d, B, max_groups), b_slices_for(d, B, max_groups), pass);     // meta offsets do not depend on n_g
     int32_t *cmin = (int32_t *)(ws + L0.cmin), *cmax = (int32_t *)(ws + L0.cmax);
     int32_t *g_first = (int32_t *)(ws + L0.g_first), *n_groups = (int32_t *)(ws + L0.n_groups);
     int32_t *cell_base = (int32_t *)(ws + L0.cell_base), *summary = (int32_t *)(ws + L0.summary);
@@ -118,7 +126,7 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     if (hipStreamSynchronize(st) != hipSuccess) return KAN_ERR_HIP;
     if (span < 2 || span > max_groups) return KAN_ERR_RANGE;
     out->n_g = span;
-    out->L = make_layout(d, B, span, out->cp.n_chunks, record_bytes_for(d, B, max_groups), pass);
+    out->L = make_layout(d, B, span, out->cp.n_chunks, record_bytes_for(d, B, max_groups), b_slices_for(d, B, max_groups), pass);
     const Layout &L = out->L;
     const int64_t rows = (int64_t)d->n_in * span;
     const int64_t n_o = (int64_t)K * d->n_out;
@@ -172,7 +180,8 @@ extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *desc, int64_t B, i
     if (check_desc(desc) != KAN_OK || B < 0 || max_groups < 2) return 0;
     if (pass != KAN_PASS_FORWARD && pass != KAN_PASS_BACKWARD) return 0;
     ChunkPlan cp = chunks_for(desc, B, max_groups);
-    return make_layout(desc, B, max_groups, cp.n_chunks, record_bytes_for(desc, B, max_groups), pass).total;
+    return make_layout(desc, B, max_groups, cp.n_chunks, record_bytes_for(desc, B, max_groups),
+                       b_slices_for(desc, B, max_groups), pass).total;
 }
 
 extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
@@ -234,7 +243,7 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
         if (launch_backward_walk(pr.g, wp, x, gy, (const float *)(w + L.cf), p->w_b, w + L.rec, fused_dx ? gx : nullptr,
                                  want_params ? part_c : nullptr, want_b ? part_b : nullptr, B, st) != hipSuccess)
             return KAN_ERR_HIP;
-        b_slices = pr.cp.n_chunks;
+        b_slices = pr.cp.n_chunks * wp.n_seg;
     } else {
         if (launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,
                                   pr.cp.chunk_len, st) != hipSuccess)

@@ -408,34 +408,40 @@ __global__ __launch_bounds__(256) void dparam_reduce_rows4_kernel(float *__restr
     if (keep_sum) *reinterpret_cast<float4 *>(part_c + at) = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
 }
 
-// 2b: gw_s from the summed acc, gw_b from the base slices.  grid (n_in, ceil(n_out / 64)), 256
-// threads: lane <-> output, the four waves split the rows (or slices) between them and their fp64
-// partial sums are added in wave order.
+// 2b: gw_s from the summed acc, gw_b from the base slices.  grid (n_in, ceil(n_out / 64), n_rs), 256
+// threads: lane <-> output, the four waves split the rows (or slices) of the block's row slice
+// between them and their fp64 partial sums are added in wave order.  With n_rs > 1 row slices the
+// block sums go to slice_sums[rs][i][j] (fp64) and dparam_reduce_edges_final_kernel adds them up in
+// slice order; with one slice the result is written directly.
 __global__ __launch_bounds__(256) void dparam_reduce_edges_kernel(const float *__restrict__ acc_sum,
                                                                   const float *__restrict__ part_b,
                                                                   const float *__restrict__ coef,
                                                                   float *__restrict__ gw_s, float *__restrict__ gw_b,
-                                                                  int n_in, int rows, int n_out, int n_slices_b)
+                                                                  double *__restrict__ slice_sums, int n_in, int rows,
+                                                                  int n_out, int n_slices_b)
 {
     __shared__ double part[2][4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = blockIdx.x, j = blockIdx.y * 64 + lane;
+    const int n_rs = gridDim.z, rs = blockIdx.z;
+    const int per = (rows + n_rs - 1) / n_rs;
+    const int m_lo = rs * per, m_hi = (m_lo + per < rows) ? m_lo + per : rows;
     const bool ok = j < n_out;
     const int jc = ok ? j : 0;
     double s = 0.0, a = 0.0;
     if (gw_s) {
         const float *cp = coef + (int64_t)i * rows * n_out + jc, *ap = acc_sum + (int64_t)i * rows * n_out + jc;
-        int m = wave;
-        for (; m + 12 < rows; m += 16) {        // four rows of this wave in flight
+        int m = m_lo + wave;
+        for (; m + 12 < m_hi; m += 16) {        // four rows of this wave in flight
             float cv[4], av[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) { cv[u] = cp[(int64_t)(m + 4 * u) * n_out]; av[u] = ap[(int64_t)(m + 4 * u) * n_out]; }
 #pragma unroll
             for (int u = 0; u < 4; ++u) s += (double)cv[u] * (double)av[u];
         }
-        for (; m < rows; m += 4) s += (double)cp[(int64_t)m * n_out] * (double)ap[(int64_t)m * n_out];
+        for (; m < m_hi; m += 4) s += (double)cp[(int64_t)m * n_out] * (double)ap[(int64_t)m * n_out];
     }
-    if (gw_b && part_b) {
+    if (gw_b && part_b && rs == 0) {
         const float *bp = part_b + (int64_t)i * n_out + jc;
         for (int c = wave; c < n_slices_b; c += 4) a += (double)bp[(int64_t)c * n_in * n_out];
     }
@@ -444,10 +450,25 @@ __global__ __launch_bounds__(256) void dparam_reduce_edges_kernel(const float *_
     __syncthreads();
     if (wave == 0 && ok) {
         const int64_t e = (int64_t)i * n_out + j;
-        if (gw_s) gw_s[e] = (float)(((part[0][0][lane] + part[0][1][lane]) + part[0][2][lane]) + part[0][3][lane]);
+        const double ss = ((part[0][0][lane] + part[0][1][lane]) + part[0][2][lane]) + part[0][3][lane];
+        if (gw_s) {
+            if (n_rs > 1) slice_sums[(int64_t)rs * n_in * n_out + e] = ss;
+            else gw_s[e] = (float)ss;
+        }
         // no base term: the gradient is identically zero
-        if (gw_b) gw_b[e] = (float)(((part[1][0][lane] + part[1][1][lane]) + part[1][2][lane]) + part[1][3][lane]);
+        if (gw_b && rs == 0) gw_b[e] = (float)(((part[1][0][lane] + part[1][1][lane]) + part[1][2][lane]) + part[1][3][lane]);
     }
+}
+
+__global__ __launch_bounds__(256) void dparam_reduce_edges_final_kernel(const double *__restrict__ slice_sums,
+                                                                        float *__restrict__ gw_s, int64_t edges,
+                                                                        int n_rs)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= edges) return;
+    double s = 0.0;
+    for (int r = 0; r < n_rs; ++r) s += slice_sums[(int64_t)r * edges + e];
+    gw_s[e] = (float)s;
 }
 
 // ---- launchers -------------------------------------------------------------
@@ -571,11 +592,21 @@ hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float 
             dparam_reduce_rows_kernel<<<(unsigned)((slab + 255) / 256), 256, 0, st>>>(part_c, w_s, gcoef, n_in, rows,
                                                                                     n_out, n_chunks, gw_s ? 1 : 0);
     }
-    (void)edges;
     if (gw_s || gw_b) {
+        // Long tables: the row sum behind gw_s is cut into row slices.  Their fp64 block sums live in
+        // the second chunk's partial slab, which is dead once the chunks have been summed.
+        int n_rs = 1;
+        double *slice_sums = nullptr;
+        if (gw_s && n_chunks >= 2 && rows >= 512) {
+            n_rs = rows / 256 < 64 ? rows / 256 : 64;
+            slice_sums = (double *)(((uintptr_t)(part_c + slab) + 7) & ~(uintptr_t)7);
+        }
         prof::Timed te("dparam_reduce_edges", st);
-        dparam_reduce_edges_kernel<<<dim3((unsigned)n_in, (unsigned)((n_out + 63) / 64)), 256, 0, st>>>(
-            part_c, part_b, coef, gw_s, gw_b, n_in, rows, n_out, n_slices_b);
+        dparam_reduce_edges_kernel<<<dim3((unsigned)n_in, (unsigned)((n_out + 63) / 64), (unsigned)n_rs), 256, 0, st>>>(
+            part_c, part_b, coef, gw_s, gw_b, slice_sums, n_in, rows, n_out, n_slices_b);
+        if (n_rs > 1)
+            dparam_reduce_edges_final_kernel<<<(unsigned)((edges + 255) / 256), 256, 0, st>>>(slice_sums, gw_s, edges,
+                                                                                            n_rs);
     }
     return hipGetLastError();
 }

@@ -119,8 +119,9 @@ extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
     if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
-    hipError_t e = narrow_applicable(g)   ? launch_forward_narrow(g, x, cf, w_b, y, B, st)
-                   : forward_lds_plan(g) ? launch_forward_lds(g, x, cf, y, B, st)
+    hipError_t e = narrow_applicable(g)    ? launch_forward_narrow(g, x, cf, w_b, y, B, st)
+                   : forward_rows_plan(g) ? launch_forward_rows(g, x, cf, y, B, st)
+                   : forward_lds_plan(g)  ? launch_forward_lds(g, x, cf, y, B, st)
                                          : launch_forward_generic(g, x, cf, w_b, y, B, st);
     return e == hipSuccess ? KAN_OK : KAN_ERR_HIP;
 }

@@ -46,6 +46,11 @@ hipError_t launch_forward_narrow(const SplineGeom &g, const float *x, const floa
 hipError_t launch_dx_narrow(const SplineGeom &g, const float *x, const float *cf, const float *w_b, const float *gy,
                             float *gx, int64_t B, hipStream_t st);
 
+// layers of 17 .. 64 outputs: four samples per wave, one per DPP row (0: not applicable)
+int forward_rows_plan(const SplineGeom &g);
+hipError_t launch_forward_rows(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
+                               hipStream_t st);
+
 // LDS-staged kernels (small grids); *_plan returns 0 when the shape does not qualify
 int forward_lds_plan(const SplineGeom &g);
 hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,

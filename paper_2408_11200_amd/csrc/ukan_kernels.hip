@@ -249,9 +249,18 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ A
     if (n >= cols) return;
     int64_t lo = (int64_t)blockIdx.y * rows_per_slice;
     int64_t hi = lo + rows_per_slice < rows ? lo + rows_per_slice : rows;
-    float s = 0.0f;
-    for (int64_t m = lo; m < hi; ++m) s += A[m * cols + n];
-    part[(int64_t)blockIdx.y * cols + n] = s;
+    // eight rows in flight; the eight running sums are combined in a fixed order
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int64_t m = lo;
+    for (; m + 8 <= hi; m += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = A[(m + u) * cols + n];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s[u] += v[u];
+    }
+    for (; m < hi; ++m) s[0] += A[m * cols + n];
+    part[(int64_t)blockIdx.y * cols + n] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
 }
 
 // sum of split-K slices: out[e] = sum_z part[z][e]

@@ -1,23 +1,26 @@
-// Parameter-gradient kernels for large grids and narrow layers, built on pair records that are
-// sorted by window row over a whole chunk of the batch.
+// Backward kernels built on pair records that are sorted by window row over a whole chunk of
+// the batch: the parameter gradients of every layer shape they cover, and dL/dx with them where
+// that is the faster way.
 //
 // With many coefficient rows per input (G + k in the hundreds, or a generated UKAN table) a tile of
 // 64 samples touches each row at most a few times, so any scheme that keeps "all rows of an input"
 // or "a block of rows" in registers spends its time on rows that receive nothing.  Here the samples
 // of one chunk (S = 256 .. 8192 samples) are sorted by the first row of their window, per input.  A
-// stream (one input, one tile of outputs, one chunk) then walks its list once: the window rows of
-// consecutive records never move backwards, so K accumulators per output slide along the rows; a
-// row is written out the moment the window has passed it and rows that no sample touched are
-// written as zeros on the way.  Work per stream is (records) x (K + 1) multiply-adds plus one
-// 16-byte store per row -- independent of the grid size (section "Algorithm": cost of the local
-// form does not grow with G).
+// stream then walks a sorted list once: the window rows of consecutive records never move
+// backwards, so K accumulators per output follow the window along the rows; a row is written out
+// the moment the window has passed it and rows that no sample touched are written as zeros on the
+// way (or jumped over).  Work per stream is (records) x (K + 1) multiply-adds plus one 16-byte
+// store per row -- independent of the grid size (section "Algorithm": cost of the local form does
+// not grow with G).
 //
-//   1. transpose_kernel     x[B][n_in] -> xT[n_in][B], so that one input's samples are contiguous
-//   2. cell_sort_kernel     per (chunk, input): stable LSD radix sort of the S samples by window row
-//                           in LDS, then one record per sample in sorted order (structure of
-//                           arrays: window row | sample, base value, the K weights)
-//   3. dparam_walk_kernel   the walk; partial sums per chunk, reduced by dparam_reduce (fp64,
-//                           fixed order), so results are bit-reproducible
+//   1. transpose_kernel      x[B][n_in] -> xT[n_in][B], so that one input's samples are contiguous
+//   2. cell_sort_kernel      per (chunk, input): stable LSD radix sort of the S samples by window row
+//                            in LDS, then one record per sample in sorted order (structure of
+//                            arrays: window row | sample, base value, the K weights)
+//   3. backward_walk_kernel  the walk; partial sums per chunk, reduced by dparam_reduce (fp64,
+//                            fixed order), so results are bit-reproducible
+//   4. walk_carry_kernel     when a list is cut into several segments (one stream each): adds what a
+//                            segment's window held past its last own row to the next segment's rows
 //
 // Lanes <-> outputs.  A wave holds 64 / LPS streams of LPS lanes each (LPS = 16, 32 or 64), so that
 // narrow layers still fill the wave.  Records are loaded 16 at a time, one per lane of each DPP row

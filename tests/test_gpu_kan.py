@@ -98,6 +98,19 @@ def test_long_run_in_one_cell():
         assert_close(g[name], ref[name], GRAD_TOL, name)
 
 
+@pytest.mark.parametrize("want", [("gx",), ("gcoef",), ("gw_b",), ("gx", "gw_s")])
+def test_gradient_subsets(want):
+    """Any subset of the gradient outputs may be requested; what is returned does not depend on the rest."""
+    w = workloads.random_kan_layer(21, 900, 6, 96, 40, 3, outside_frac=0.2)
+    s, p = w.layers[0], w.params[0]
+    inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+    g = binding.kan_backward(s, dev(w.x), dev(p["coef"]), dev(p["w_s"]), dev(p["w_b"]), dev(w.gy), want=want)
+    assert set(g) == set(want)
+    ref = oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h)
+    for name in want:
+        assert_close(g[name], ref[name], GRAD_TOL, name)
+
+
 def test_no_base_term():
     w = workloads.random_kan_layer(5, 100, 6, 64, 8, 3, base_act=0, outside_frac=0.3)
     s, p = w.layers[0], w.params[0]

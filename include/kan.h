@@ -169,6 +169,15 @@ int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const float *x, con
                      const float *gy, float *gx, const ukan_grads *g, int32_t max_groups, void *ws,
                      size_t ws_bytes, void *stream);
 
+/* UKAN -> KAN export (appendix "Converting UKAN to KAN"): the coefficients of the bounded-grid layer that
+   equals this UKAN layer on the cells cell_lo .. cell_hi, i.e. on [cell_lo*h, (cell_hi+1)*h):
+     coef[i][m][j] = scale[i][j] * CG(i, g)[q*n_out + j],   g*K + q = cell_lo - K + m,   m = 0 .. G + k - 1,
+   G = cell_hi - cell_lo + 1.  Use it with kan_layer_desc{n_in, n_out, G, k, cell_lo*h, (cell_hi+1)*h, base_act},
+   w_s = 1 and the same w_b.  coef is [n_in][G + k][n_out], device memory, 16-byte aligned.  Does not synchronise. */
+size_t ukan_materialize_workspace_bytes(const ukan_layer_desc *desc, int64_t cell_lo, int64_t cell_hi);
+int ukan_materialize(const ukan_layer_desc *desc, const ukan_params *p, int64_t cell_lo, int64_t cell_hi,
+                     float *coef, void *ws, size_t ws_bytes, void *stream);
+
 /* Parity aid: cell, group and within-group offset of x[p], p < n (any output may be NULL). */
 int ukan_group_index(const ukan_layer_desc *desc, int64_t n, const float *x, int32_t *cell,
                      int32_t *group, int32_t *offset, void *stream);

@@ -23,7 +23,8 @@ PASS_FORWARD, PASS_BACKWARD = 0, 1
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
            "kan_profile_enable", "kan_profile_read", "kan_dense_baseline_workspace_bytes",
            "kan_dense_baseline_forward",
-           "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_group_index"]
+           "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_materialize_workspace_bytes",
+           "ukan_materialize", "ukan_group_index"]
 
 
 class KanLayerDesc(ctypes.Structure):
@@ -94,6 +95,10 @@ def load():
     lib.ukan_cg_backward.restype = ctypes.c_int
     lib.ukan_cg_backward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, vp,
                                      ctypes.POINTER(UkanGrads), i32, vp, sz, vp]
+    lib.ukan_materialize_workspace_bytes.restype = ctypes.c_size_t
+    lib.ukan_materialize_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i64]
+    lib.ukan_materialize.restype = ctypes.c_int
+    lib.ukan_materialize.argtypes = [ctypes.POINTER(UkanLayerDesc), ctypes.POINTER(UkanParams), i64, i64, vp, vp, sz, vp]
     lib.ukan_group_index.restype = ctypes.c_int
     lib.ukan_group_index.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, vp, vp, vp, vp]
     _lib = lib
@@ -269,6 +274,24 @@ def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, s
     if rc != KAN_OK:
         raise KanError(rc, "ukan_cg_backward")
     return out
+
+
+def ukan_materialize(spec, p, cell_lo, cell_hi, coef=None, ws=None, stream=None):
+    """Coefficients [n_in][cell_hi - cell_lo + 1 + k][n_out] of the KAN layer equal to this UKAN layer on the cells."""
+    lib = load()
+    d = ukan_desc(spec)
+    dev = p["E"].device
+    if coef is None:
+        coef = torch.empty((spec.n_in, int(cell_hi) - int(cell_lo) + 1 + spec.k, spec.n_out), dtype=torch.float32,
+                           device=dev)
+    if ws is None:
+        ws = _workspace(lib.ukan_materialize_workspace_bytes(ctypes.byref(d), int(cell_lo), int(cell_hi)), dev)
+    pp = _ukan_params(p)
+    rc = lib.ukan_materialize(ctypes.byref(d), ctypes.byref(pp), int(cell_lo), int(cell_hi), _f32(coef), _ptr(ws),
+                              ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "ukan_materialize")
+    return coef
 
 
 def ukan_group_index(spec, x, stream=None):

@@ -301,6 +301,72 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     return KAN_OK;
 }
 
+namespace {
+inline int64_t floordiv64(int64_t a, int64_t b) { int64_t q = a / b; return (a % b != 0 && ((a < 0) != (b < 0))) ? q - 1 : q; }
+
+// groups the export needs: global coefficients cell_lo - K .. cell_hi - 1
+struct ExportPlan { int64_t g_first, n_g; size_t gf_off, hid_off, table_off, total; };
+bool export_plan(const ukan_layer_desc *d, int64_t cell_lo, int64_t cell_hi, ExportPlan *e)
+{
+    const int64_t K = d->k + 1;
+    if (cell_hi < cell_lo || cell_lo < -(1ll << 30) || cell_hi > (1ll << 30)) return false;
+    e->g_first = floordiv64(cell_lo - K, K);
+    e->n_g = floordiv64(cell_hi - 1, K) - e->g_first + 1;
+    if (e->n_g < 1 || e->n_g > (1 << 20)) return false;
+    const size_t rows = (size_t)d->n_in * (size_t)e->n_g;
+    size_t at = 0;
+    e->gf_off = at;    at += align_up((size_t)d->n_in * 4);
+    e->hid_off = at;   at += align_up(rows * d->d_hidden * 4);
+    e->table_off = at; at += align_up(rows * K * d->n_out * 4);
+    e->total = at;
+    return true;
+}
+}  // namespace
+
+extern "C" size_t ukan_materialize_workspace_bytes(const ukan_layer_desc *desc, int64_t cell_lo, int64_t cell_hi)
+{
+    ExportPlan e;
+    if (check_desc(desc) != KAN_OK || !export_plan(desc, cell_lo, cell_hi, &e)) return 0;
+    return e.total;
+}
+
+extern "C" int ukan_materialize(const ukan_layer_desc *desc, const ukan_params *p, int64_t cell_lo, int64_t cell_hi,
+                                float *coef, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != KAN_OK) return rc;
+    ExportPlan e;
+    if (!export_plan(desc, cell_lo, cell_hi, &e)) return KAN_ERR_INVALID_ARG;
+    if (!p || !p->E || !p->W1 || !p->b1 || !p->W2 || !p->b2 || !p->scale || !coef) return KAN_ERR_INVALID_ARG;
+    if (((uintptr_t)coef % 16) != 0) return KAN_ERR_INVALID_ARG;
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < e.total) return KAN_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *w = (char *)ws;
+    const int K = desc->k + 1;
+    int32_t *g_first = (int32_t *)(w + e.gf_off);
+    float *hid = (float *)(w + e.hid_off), *table = (float *)(w + e.table_off);
+    if (launch_fill_int(g_first, (int32_t)e.g_first, desc->n_in, st) != hipSuccess) return KAN_ERR_HIP;
+    if (launch_cg_hidden(p->E, p->W1, p->b1, g_first, nullptr, nullptr, hid, desc->n_in, (int)e.n_g, desc->d_pe,
+                         desc->d_feat, desc->d_hidden, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    const int64_t n_o = (int64_t)K * desc->n_out;
+    GemmArgs a = {};
+    a.A = hid; a.a_rs = desc->d_hidden; a.a_cs = 1;
+    a.B = p->W2; a.b_rs = n_o; a.b_cs = 1;
+    a.C = table; a.ldc = n_o;
+    a.M = (int64_t)desc->n_in * e.n_g; a.N = n_o; a.K = desc->d_hidden;
+    a.k_slice = desc->d_hidden; a.c_slice = 0;
+    a.bias = p->b2; a.scale = p->scale; a.C2 = nullptr;
+    a.rows_per_input = e.n_g; a.n_out = desc->n_out;
+    if (launch_gemm(a, EPI_CG_OUT, 1, "cg_output_gemm", st) != hipSuccess) return KAN_ERR_HIP;
+    // table row r of an input is global coefficient g_first*K + r; coef row m is global coefficient cell_lo - K + m
+    const int shift = (int)(cell_lo - K - e.g_first * K);
+    const int coef_rows = (int)(cell_hi - cell_lo + 1) + desc->k;
+    if (launch_table_rows(table, coef, desc->n_in, (int)(e.n_g * K), coef_rows, shift, desc->n_out, st) != hipSuccess)
+        return KAN_ERR_HIP;
+    return KAN_OK;
+}
+
 extern "C" int ukan_group_index(const ukan_layer_desc *desc, int64_t n, const float *x, int32_t *cell,
                                 int32_t *group, int32_t *offset, void *stream)
 {

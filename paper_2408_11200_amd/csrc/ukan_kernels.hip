@@ -295,7 +295,40 @@ __global__ __launch_bounds__(256) void embed_grad_kernel(const float *__restrict
     }
 }
 
+// UKAN -> KAN export: every input uses the same first group; coef[i][m][j] = table row (m + shift)
+__global__ __launch_bounds__(256) void fill_int_kernel(int32_t *__restrict__ p, int32_t v, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void table_rows_kernel(const float *__restrict__ table, float *__restrict__ coef,
+                                                         int n_in, int table_rows, int coef_rows, int shift, int n_out)
+{
+    const int64_t at = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (at >= (int64_t)n_in * coef_rows * n_out) return;
+    const int j = (int)(at % n_out);
+    const int m = (int)((at / n_out) % coef_rows);
+    const int i = (int)(at / ((int64_t)n_out * coef_rows));
+    coef[at] = table[((int64_t)i * table_rows + m + shift) * n_out + j];
+}
+
 // ---- launchers ----------------------------------------------------------------------
+
+hipError_t launch_fill_int(int32_t *p, int32_t v, int n, hipStream_t st)
+{
+    fill_int_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, v, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_table_rows(const float *table, float *coef, int n_in, int table_rows, int coef_rows, int shift,
+                             int n_out, hipStream_t st)
+{
+    const int64_t n = (int64_t)n_in * coef_rows * n_out;
+    prof::Timed tm("ukan_table_rows", st);
+    table_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(table, coef, n_in, table_rows, coef_rows, shift, n_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_slice_sum(const float *part, float *out, int64_t n, int slices, hipStream_t st);
 

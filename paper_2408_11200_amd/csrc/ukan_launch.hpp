@@ -33,6 +33,9 @@ hipError_t launch_range(const float *x, int64_t B, int n_in, float inv_h, int K,
 hipError_t launch_cg_hidden(const float *E, const float *W1, const float *b1, const int32_t *g_first, float *z,
                             float *pre, float *hid, int n_in, int n_g, int d_pe, int d_feat, int d_hid,
                             hipStream_t st);
+hipError_t launch_fill_int(int32_t *p, int32_t v, int n, hipStream_t st);
+hipError_t launch_table_rows(const float *table, float *coef, int n_in, int table_rows, int coef_rows, int shift,
+                             int n_out, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &a, int epi, int slices, const char *family, hipStream_t st);
 hipError_t launch_colsum(const float *A, float *part, float *out, int64_t rows, int cols, hipStream_t st);
 hipError_t launch_slice_sum(const float *part, float *out, int64_t n, int slices, hipStream_t st);

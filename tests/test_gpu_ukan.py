@@ -100,6 +100,27 @@ def test_ukan_equals_kan_on_materialised_table():
     assert_close(y_ukan, ref, 2e-5, "ukan vs kan")
 
 
+def test_ukan_materialize_matches_oracle_and_ukan_forward():
+    """The exported table equals the oracle's, also for negative cells and a range that starts inside a
+    group; kan_forward on it reproduces ukan_cg_forward."""
+    spec, p, x, gy = make(9, 600, 5, 32, xs=2.5)
+    P = {n: dev(a) for n, a in p.items()}
+    for c_lo, c_hi in [(-13, 9), (2, 2), (-3, -1), (0, 40)]:
+        got = binding.ukan_materialize(spec, P, c_lo, c_hi)
+        assert_close(got, oracle.ukan_materialize(p, 3, c_lo, c_hi), 1e-5, "table %d..%d" % (c_lo, c_hi))
+    inv_h = oracle.inv_h_of_spacing(spec.h)
+    cell, _, _ = oracle.group_index(x, inv_h, 4)
+    c_lo, c_hi = int(cell.min()), int(cell.max())
+    coef = binding.ukan_materialize(spec, P, c_lo, c_hi)
+    kspec = workloads.KanLayerSpec(5, 32, c_hi - c_lo + 1, 3, c_lo * spec.h, (c_hi + 1) * spec.h, base_act=0)
+    y_kan = binding.kan_forward(kspec, dev(x), coef, torch.ones((5, 32), device="cuda"), None)
+    y_ukan = binding.ukan_cg_forward(spec, dev(x), P, 64)
+    assert_close(y_ukan, y_kan.double().cpu().numpy(), 2e-5, "ukan vs kan on the exported table")
+    lib = binding.load()
+    import ctypes
+    assert lib.ukan_materialize_workspace_bytes(ctypes.byref(binding.ukan_desc(spec)), 5, 4) == 0
+
+
 def test_ukan_range_error_and_arguments():
     spec, p, x, gy = make(7, 64, 3, 8)
     pd = {n: dev(a) for n, a in p.items()}

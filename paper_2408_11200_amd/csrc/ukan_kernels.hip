@@ -156,8 +156,10 @@ template <int EPI, bool ACC64>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a)
 {
     constexpr int BM = 64, BN = 64, BK = 16, PAD = 4;
-    __shared__ float As[BK][BM + PAD];
-    __shared__ float Bs[BK][BN + PAD];
+    // two LDS stages: the next K step is fetched into registers while the current one is multiplied,
+    // then parked in the other stage; one barrier per step
+    __shared__ float As[2][BK][BM + PAD];
+    __shared__ float Bs[2][BK][BN + PAD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int64_t k_lo = (int64_t)blockIdx.z * a.k_slice;
@@ -175,34 +177,56 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a)
 #pragma unroll
             for (int v = 0; v < 4; ++v) dacc[bi][bj][v] = 0.0;
 
-    int step = 0;
+    // A[BM x BK] and B[BK x BN] of one K step: four elements of each per thread; the thread -> element
+    // map follows whichever stride is 1
+    constexpr int PER = BM * BK / 256;
+    float ra[PER], rb[PER];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid + u * 256;
+            int mm, kk;
+            if (a.a_cs == 1) { kk = e % BK; mm = e / BK; } else { mm = e % BM; kk = e / BM; }
+            const int64_t m = m0 + mm, k = k0 + kk;
+            ra[u] = (m < a.M && k < k_hi) ? a.A[m * a.a_rs + k * a.a_cs] : 0.0f;
+            int nn;
+            if (a.b_cs == 1) { nn = e % BN; kk = e / BN; } else { kk = e % BK; nn = e / BK; }
+            const int64_t n = n0 + nn, kb = k0 + kk;
+            rb[u] = (n < a.N && kb < k_hi) ? a.B[kb * a.b_rs + n * a.b_cs] : 0.0f;
+        }
+    };
+    auto park = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid + u * 256;
+            int mm, kk;
+            if (a.a_cs == 1) { kk = e % BK; mm = e / BK; } else { mm = e % BM; kk = e / BM; }
+            As[buf][kk][mm] = ra[u];
+            int nn;
+            if (a.b_cs == 1) { nn = e % BN; kk = e / BN; } else { kk = e % BK; nn = e / BK; }
+            Bs[buf][kk][nn] = rb[u];
+        }
+    };
+
+    int step = 0, buf = 0;
+    if (k_lo < k_hi) {
+        fetch(k_lo);
+        park(0);
+    }
+    __syncthreads();
     for (int64_t k0 = k_lo; k0 < k_hi; k0 += BK, ++step) {
         if (!ACC64 && (step & 3) == 0 && step > 0) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) { tot[v] += acc[v]; acc[v] = 0.0f; }
         }
-        // stage A[BM x BK] and B[BK x BN]; the thread -> element map follows whichever stride is 1
-#pragma unroll
-        for (int e = tid; e < BM * BK; e += 256) {
-            int mm, kk;
-            if (a.a_cs == 1) { kk = e % BK; mm = e / BK; } else { mm = e % BM; kk = e / BM; }
-            int64_t m = m0 + mm, k = k0 + kk;
-            As[kk][mm] = (m < a.M && k < k_hi) ? a.A[m * a.a_rs + k * a.a_cs] : 0.0f;
-        }
-#pragma unroll
-        for (int e = tid; e < BK * BN; e += 256) {
-            int nn, kk;
-            if (a.b_cs == 1) { nn = e % BN; kk = e / BN; } else { kk = e % BK; nn = e / BK; }
-            int64_t n = n0 + nn, k = k0 + kk;
-            Bs[kk][nn] = (n < a.N && k < k_hi) ? a.B[k * a.b_rs + n * a.b_cs] : 0.0f;
-        }
-        __syncthreads();
+        const bool more = k0 + BK < k_hi;
+        if (more) fetch(k0 + BK);
         if constexpr (ACC64) {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 4) {
                 const int kr = kk + (lane >> 4), c = lane & 15;
-                const double a0 = (double)As[kr][wm + c], a1 = (double)As[kr][wm + 16 + c];
-                const double b0 = (double)Bs[kr][wn + c], b1 = (double)Bs[kr][wn + 16 + c];
+                const double a0 = (double)As[buf][kr][wm + c], a1 = (double)As[buf][kr][wm + 16 + c];
+                const double b0 = (double)Bs[buf][kr][wn + c], b1 = (double)Bs[buf][kr][wn + 16 + c];
                 dacc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, dacc[0][0], 0, 0, 0);
                 dacc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, dacc[0][1], 0, 0, 0);
                 dacc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, dacc[1][0], 0, 0, 0);
@@ -211,12 +235,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a)
         } else {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 2) {
-                float av = As[kk + (lane >> 5)][wm + (lane & 31)];
-                float bv = Bs[kk + (lane >> 5)][wn + (lane & 31)];
+                float av = As[buf][kk + (lane >> 5)][wm + (lane & 31)];
+                float bv = Bs[buf][kk + (lane >> 5)][wn + (lane & 31)];
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
             }
         }
+        if (more) park(buf ^ 1);
         __syncthreads();
+        buf ^= 1;
     }
 
     float *C = a.C + (int64_t)blockIdx.z * a.c_slice;

@@ -5,4 +5,4 @@ The compute lives in the HIP library built from `csrc/` (C ABI declared in
 point names.  Importing this package does not load the library; the first call
 into `binding` does, and fails loudly when it has not been built.
 """
-__all__ = ["binding", "workloads", "roofline"]
+__all__ = ["binding", "autograd", "workloads", "roofline"]

@@ -256,19 +256,28 @@ __device__ __forceinline__ void static_for(F &&f)
 template <int T>
 __device__ __forceinline__ void load_vec(const float *p, float (&v)[T])
 {
-    if constexpr (T == 4) {
+    if constexpr (T == 8) {
+        const float4 t = *reinterpret_cast<const float4 *>(p), u = *reinterpret_cast<const float4 *>(p + 4);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; v[4] = u.x; v[5] = u.y; v[6] = u.z; v[7] = u.w;
+    } else if constexpr (T == 4) {
         const float4 t = *reinterpret_cast<const float4 *>(p);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
-        static_assert(T == 1, "one or four outputs per lane");
+        static_assert(T == 1, "one, four or eight outputs per lane");
         v[0] = *p;
     }
 }
 template <int T>
 __device__ __forceinline__ void store_vec(float *p, const float (&v)[T])
 {
-    if constexpr (T == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    else p[0] = v[0];
+    if constexpr (T == 8) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else if constexpr (T == 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        p[0] = v[0];
+    }
 }
 
 // 4 waves per block, STREAMS streams per wave.  Per record: one gather of the sample's gy row
@@ -439,17 +448,20 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
         const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
         float dot[16];
-        auto half = [&](auto h) {
+        // the 16 records go in groups whose gy rows are gathered together (fewer at eight outputs per
+        // lane, to bound the registers in flight)
+        constexpr int GROUP = T == 8 ? 4 : 8;
+        auto group = [&](auto h) {
             constexpr int H = decltype(h)::value;
-            float gr[8][T];
-            static_for<0, 8>([&](auto n) {
+            float gr[GROUP][T];
+            static_for<0, GROUP>([&](auto n) {
                 constexpr int N = decltype(n)::value;
-                const int t = row_bcast<H * 8 + N>(tv);
+                const int t = row_bcast<H * GROUP + N>(tv);
                 load_vec<T>(gyp + (int64_t)t * g.n_out, gr[N]);
             });
-            static_for<0, 8>([&](auto n) {
+            static_for<0, GROUP>([&](auto n) {
                 constexpr int N = decltype(n)::value;
-                constexpr int R = H * 8 + N;
+                constexpr int R = H * GROUP + N;
                 const int row0 = row_bcast<R>(rowv);
                 if (row0 - cur >= kMaxK) {
                     // the window jumps clear of its old position: write it out whole and start afresh
@@ -492,8 +504,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                 }
             });
         };
-        half(std::integral_constant<int, 0>{});
-        half(std::integral_constant<int, 1>{});
+        static_for<0, 16 / GROUP>(group);
         if constexpr (DX) {
             const float total = reduce_levels<LPS / 2, 16>(dot, lane);
             const int qn = quantity_of<LPS>(lane);
@@ -586,7 +597,10 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
 {
     WalkPlan p = {};
     if (g.rows < kMaxK || g.rows > 0xffff || B < 1) return p;
-    if (g.n_out % 4 == 0) {
+    if (g.n_out % 8 == 0 && g.n_out > 256) {
+        p.T = 8;            // one tile covers 512 outputs: the per-record work is shared by twice as many
+        p.streams = 1;
+    } else if (g.n_out % 4 == 0) {
         p.T = 4;
         p.streams = g.n_out > 128 ? 1 : (g.n_out > 64 ? 2 : 4);
     } else if (g.n_out <= 16) {
@@ -708,7 +722,9 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     }
     {
         prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
-        if (p.T == 4 && p.streams == 1)
+        if (p.T == 8 && p.streams == 1)
+            walk_launch<1, 8>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
+        else if (p.T == 4 && p.streams == 1)
             walk_launch<1, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
         else if (p.T == 4 && p.streams == 2)
             walk_launch<2, 4>(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);

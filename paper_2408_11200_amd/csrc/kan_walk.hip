@@ -448,6 +448,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
         const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
         float dot[16];
+        bool quad_same = false;
         // the 16 records go in groups whose gy rows are gathered together (fewer at eight outputs per
         // lane, to bound the registers in flight)
         constexpr int GROUP = T == 8 ? 4 : 8;
@@ -484,23 +485,50 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                     asm volatile("" : "+v"(ab[r]));     // keep the base term with its record (see below)
                 }
                 if constexpr (DX) {
-                    const float d0 = row_bcast<R>(mine.dw[0]), d1 = row_bcast<R>(mine.dw[1]);
-                    const float d2 = row_bcast<R>(mine.dw[2]), d3 = row_bcast<R>(mine.dw[3]);
-                    const float db = row_bcast<R>(mine.dbase);
-                    float acc = 0.0f;
+                    // Four consecutive records with the same window (the common case on small grids, where
+                    // a cell holds many samples of the chunk) share the table rows: their
+                    // q_j = sum_s dw_s c_s[j] + dbase w_b[j] are rank-1 updates again, one matrix-core
+                    // instruction per window row and output register for all four (A = the four records'
+                    // dw_s, broadcast from the lanes that hold them; B = the lane's table entry).
+                    if constexpr (R % 4 == 0) quad_same = row_bcast<R>(rowv) == row_bcast<R + 3>(rowv);
+                    if (!quad_same) {
+                        const float d0 = row_bcast<R>(mine.dw[0]), d1 = row_bcast<R>(mine.dw[1]);
+                        const float d2 = row_bcast<R>(mine.dw[2]), d3 = row_bcast<R>(mine.dw[3]);
+                        const float db = row_bcast<R>(mine.dbase);
+                        float acc = 0.0f;
 #pragma unroll
-                    for (int r = 0; r < T; ++r) {
-                        float qv = d0 * cw[0][r];
-                        qv = fmaf(d1, cw[1][r], qv);
-                        qv = fmaf(d2, cw[2][r], qv);
-                        qv = fmaf(d3, cw[3][r], qv);
-                        qv = fmaf(db, wb[r], qv);
-                        acc = fmaf(gr[N][r], qv, acc);
+                        for (int r = 0; r < T; ++r) {
+                            float qv = d0 * cw[0][r];
+                            qv = fmaf(d1, cw[1][r], qv);
+                            qv = fmaf(d2, cw[2][r], qv);
+                            qv = fmaf(d3, cw[3][r], qv);
+                            qv = fmaf(db, wb[r], qv);
+                            acc = fmaf(gr[N][r], qv, acc);
+                        }
+                        // pin the dot product here: left alone, the compiler sinks all sixteen of them below
+                        // the last record and keeps a copy of the table rows per record alive until then
+                        asm volatile("" : "+v"(acc));
+                        dot[R] = acc;
                     }
-                    // pin the dot product here: left alone, the compiler sinks all sixteen of them below the
-                    // last record and keeps a copy of the table rows per record alive until then
-                    asm volatile("" : "+v"(acc));
-                    dot[R] = acc;
+                    if constexpr (R % 4 == 3) {
+                        if (quad_same) {
+                            float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                            for (int r = 0; r < T; ++r) {
+                                f32x4 qv = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                                for (int s = 0; s < kMaxK; ++s) rank1_update<CBSZ, R / 4>(qv, mine.dw[s], cw[s][r]);
+                                rank1_update<CBSZ, R / 4>(qv, mine.dbase, wb[r]);
+#pragma unroll
+                                for (int u = 0; u < 4; ++u) acc[u] = fmaf(gr[N - 3 + u][r], qv[u], acc[u]);
+                            }
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                asm volatile("" : "+v"(acc[u]));
+                                dot[R - 3 + u] = acc[u];
+                            }
+                        }
+                    }
                 }
             });
         };

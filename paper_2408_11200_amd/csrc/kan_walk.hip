@@ -302,7 +302,7 @@ __device__ __forceinline__ void rank1_update(f32x4 &acc, float a_quads, float b)
     acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a_quads, b, acc, CBSZ, ABID, 0);
 }
 
-template <int STREAMS, int T, bool DX>
+template <int STREAMS, int T, bool DX, bool FOLD>
 __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRecords rec,
                                                             const float *__restrict__ gy,
                                                             const float *__restrict__ cf,
@@ -348,12 +348,19 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     float *gxo = DX ? gx + (int64_t)jt * B * g.n_in + b0 * g.n_in + i : nullptr;
 
     // a[r][s]: running sum of output j + r, window row cur + s; hi: the second level
-    f32x4 a[T], hi[T];
-    float ab[T], abh[T], zero[T];
+    // (FOLD == false: chunks of at most 1024 samples, one level is accurate enough and the registers
+    // of the second go to keeping more gy rows in flight)
+    constexpr int TH = FOLD ? T : 1;
+    f32x4 a[T], hi[TH];
+    float ab[T], abh[TH], zero[T];
 #pragma unroll
     for (int r = 0; r < T; ++r) {
-        ab[r] = 0.0f; abh[r] = 0.0f; zero[r] = 0.0f;
+        ab[r] = 0.0f; zero[r] = 0.0f;
         a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+#pragma unroll
+    for (int r = 0; r < TH; ++r) {
+        abh[r] = 0.0f;
         hi[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
 
@@ -379,9 +386,12 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         constexpr int SL = decltype(sl)::value;
 #pragma unroll
         for (int r = 0; r < T; ++r) {
-            gone[r] = a[r][SL] + hi[r][SL];
+            gone[r] = a[r][SL];
             a[r][SL] = 0.0f;
-            hi[r][SL] = 0.0f;
+            if constexpr (FOLD) {
+                gone[r] += hi[r][SL];
+                hi[r][SL] = 0.0f;
+            }
         }
         if (store && store_c) store_vec<T>(out + (int64_t)cur * g.n_out, gone);
         if (DX && enter_next) {
@@ -444,22 +454,29 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     // included (zero weights, sorted last)
     const int nb = seg_len / 16;
     Batch mine = load_batch(0);
+    float gbuf[2][4][T];
+    auto gather = [&](int tv_of_batch, auto h, float (&dst)[4][T]) {
+        constexpr int H = decltype(h)::value;
+        static_for<0, 4>([&](auto n) {
+            constexpr int N = decltype(n)::value;
+            const int t = row_bcast<H * 4 + N>(tv_of_batch);
+            load_vec<T>(gyp + (int64_t)t * g.n_out, dst[N]);
+        });
+    };
+    gather((int)((unsigned)mine.rt >> 16), std::integral_constant<int, 0>{}, gbuf[0]);
     for (int bi = 0; bi < nb; ++bi) {
         const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
         const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
         float dot[16];
         bool quad_same = false;
-        // the 16 records go in groups whose gy rows are gathered together (fewer at eight outputs per
-        // lane, to bound the registers in flight)
-        constexpr int GROUP = T == 8 ? 4 : 8;
+        // The 16 records go in groups of four.  The gy rows of the next group (the first of the next
+        // batch after the last) are requested before the current group is worked on.
+        constexpr int GROUP = 4;
         auto group = [&](auto h) {
             constexpr int H = decltype(h)::value;
-            float gr[GROUP][T];
-            static_for<0, GROUP>([&](auto n) {
-                constexpr int N = decltype(n)::value;
-                const int t = row_bcast<H * GROUP + N>(tv);
-                load_vec<T>(gyp + (int64_t)t * g.n_out, gr[N]);
-            });
+            auto &gr = gbuf[H & 1];
+            if constexpr (H + 1 < 16 / GROUP) gather(tv, std::integral_constant<int, H + 1>{}, gbuf[(H + 1) & 1]);
+            else gather((int)((unsigned)upcoming.rt >> 16), std::integral_constant<int, 0>{}, gbuf[0]);
             static_for<0, GROUP>([&](auto n) {
                 constexpr int N = decltype(n)::value;
                 constexpr int R = H * GROUP + N;
@@ -539,12 +556,14 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
             const int t = __shfl(tv, (lane & ~15) | qn, 64);
             if ((lane % (LPS / 16)) == 0 && seg * seg_len + bi * 16 + qn < n_c) gxo[(int64_t)t * g.n_in] = total;
         }
-        if ((bi & 15) == 15) {
+        if constexpr (FOLD) {
+            if ((bi & 15) == 15) {
 #pragma unroll
-            for (int r = 0; r < T; ++r) {
-                hi[r] += a[r];
-                a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                abh[r] += ab[r]; ab[r] = 0.0f;
+                for (int r = 0; r < T; ++r) {
+                    hi[r] += a[r];
+                    a[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                    abh[r] += ab[r]; ab[r] = 0.0f;
+                }
             }
         }
         mine = upcoming;
@@ -568,7 +587,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     if (part_b) {
         float o[T];
 #pragma unroll
-        for (int r = 0; r < T; ++r) o[r] = ab[r] + abh[r];
+        for (int r = 0; r < T; ++r) o[r] = FOLD ? ab[r] + abh[r < TH ? r : 0] : ab[r];
         store_vec<T>(part_b + (((int64_t)c * n_seg + seg) * g.n_in + i) * g.n_out + jc, o);
     }
 }
@@ -689,14 +708,10 @@ static void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGe
                         const float *gy, const float *cf, const float *w_b, float *part_c, float *part_b, float *gx,
                         int64_t B, const WalkPlan &p, int bpc, int m, int prezeroed, float *carry)
 {
-    if (dx)
-        backward_walk_kernel<STREAMS, T, true><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
-                                                                      p.n_chunks, p.n_jt, bpc, m, prezeroed, p.n_seg,
-                                                                      carry);
-    else
-        backward_walk_kernel<STREAMS, T, false><<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S,
-                                                                       p.n_chunks, p.n_jt, bpc, m, prezeroed, p.n_seg,
-                                                                       carry);
+    auto kern = dx ? (p.S > 1024 ? backward_walk_kernel<STREAMS, T, true, true> : backward_walk_kernel<STREAMS, T, true, false>)
+                   : (p.S > 1024 ? backward_walk_kernel<STREAMS, T, false, true> : backward_walk_kernel<STREAMS, T, false, false>);
+    kern<<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S, p.n_chunks, p.n_jt, bpc, m, prezeroed,
+                                 p.n_seg, carry);
 }
 
 // gx == nullptr: parameter gradients only.  part_c == nullptr: dL/dx only.  cf is the scale-folded

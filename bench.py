@@ -31,15 +31,13 @@ def flops_per_edge(k):
 # that workload and these kernels.
 MEASURED_TRAFFIC_BYTES_C3 = {
     "forward_lds": 235.3e6 + 33.6e6,
-    "dx_lds": 268.5e6 + 33.6e6,
-    "dparam_walk": 437.0e6 + 402.7e6,
 }
 
 # kernel family -> which third of the fwd+bwd work it carries ("backward" = dL/dx and the parameter
 # gradients in one kernel: two thirds)
 KERNEL_ROLE = {
     "forward_generic": "forward", "dx_generic": "dx", "dparam_generic": "dparam",
-    "forward_lds": "forward", "dx_lds": "dx", "dparam_walk": "dparam", "backward_walk": "backward",
+    "forward_lds": "forward", "forward_rows": "forward", "dparam_walk": "dparam", "backward_walk": "backward",
     "forward_narrow": "forward", "dx_narrow": "dx",
 }
 ROLE_SHARE = {"forward": 1, "dx": 1, "dparam": 1, "backward": 2}
@@ -214,7 +212,9 @@ def main():
     else:
         flops, achieved = None, None
     peak = roofline.MI355X_FP32_VECTOR_FLOPS / 1e12
-    rl = {"bound": "alu", "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+    # the walk kernels run the window-row multiply-adds on the matrix cores (fp32 MFMA peak = fp32 vector peak)
+    bound = "mfma" if dom in ("backward_walk", "dparam_walk") else "alu"
+    rl = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
           "frac": (achieved / peak) if achieved else None,
           "traffic": MEASURED_TRAFFIC_BYTES_C3.get(dom) if args.workload == "c3" else None,
           "kernel_ms": dom_ms / max(launches[dom], 1), "kernel_launches_per_step": launches[dom],

@@ -146,15 +146,12 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     float *cf = (float *)ws;
     const BackwardPlan bp = backward_plan(desc, B);
     const bool want_params = gcoef || gw_s || gw_b;
-    // The chunk-sorted walk takes dL/dx together with the parameter gradients (one pass over gy),
-    // except for small-grid layers wider than one output tile, where the LDS-staged dL/dx kernel with
-    // its eight outputs per lane is the faster of the two.
-    const bool fused_dx = gx && bp.walk && !(bp.wp.n_jt > 1 && dx_lds_plan(g));
+    // the chunk-sorted walk takes dL/dx together with the parameter gradients (one pass over gy)
+    const bool fused_dx = gx && bp.walk;
     if (gx) {
         if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
         if (!fused_dx) {
             hipError_t e = narrow_applicable(g) ? launch_dx_narrow(g, x, cf, w_b, gy, gx, B, st)
-                           : dx_lds_plan(g)     ? launch_dx_lds(g, x, cf, gy, gx, B, st)
                                                 : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
             if (e != hipSuccess) return KAN_ERR_HIP;
         }

@@ -56,10 +56,6 @@ int forward_lds_plan(const SplineGeom &g);
 hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
                               hipStream_t st);
 
-int dx_lds_plan(const SplineGeom &g);
-hipError_t launch_dx_lds(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx, int64_t B,
-                         hipStream_t st);
-
 // Sorted pair records of the walk, one per (sample, input) pair, as a structure of arrays indexed
 // [chunk][input][rank in the chunk's sorted order]: first row of the K-wide window (clamped into the
 // table) | the sample's index inside its chunk << 16; the base value; the K window weights (16-byte

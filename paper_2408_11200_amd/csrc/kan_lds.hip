@@ -1,4 +1,4 @@
-// LDS-staged kernels of the local B-spline layer for grids whose per-input coefficient
+// LDS-staged forward kernel of the local B-spline layer for grids whose per-input coefficient
 // slab fits in LDS (the common case: G + k up to a few dozen rows).
 //
 // A workgroup of NW waves owns NW*T samples and a tile of TJ = 64*R outputs.  It walks over
@@ -224,133 +224,6 @@ __global__ __launch_bounds__(64 * NW) void forward_lds_kernel(SplineGeom g, cons
     }
 }
 
-// ---- backward: dL/dx ---------------------------------------------------------------
-// Same staging as the forward kernel (TJ must cover every output, so that one wave sees the whole
-// sum over j).  A wave keeps gy of its T samples in registers; per (sample, input) pair each lane
-// forms   p = sum_s dw_s * (sum_r gy_r * c_s[r]) + dbase * (sum_r gy_r * wb[r])   over its R outputs,
-// and the T partial vectors of one input are reduced over the 64 lanes together: a halving butterfly
-// leaves the total of sample t in the 64/T lanes whose upper lane bits equal t.
-namespace {
-
-__device__ __forceinline__ float dpp_xor1(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float dpp_xor2(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float dpp_half_mirror(float v)      // lane l <-> l ^ 7 within 8
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float dpp_mirror(float v)           // lane l <-> l ^ 15 within 16
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
-}
-
-// q[0..N) hold, per lane, partial sums of N different quantities.  Returns in every lane the
-// quantity number (lane / (64/N)) summed over the 64/N... over ALL 64 lanes.
-template <int N>
-__device__ __forceinline__ float reduce_transposed(float (&q)[N], int lane)
-{
-    static_assert(N == 4, "written for four quantities per round");
-    // 4 -> 2 on lane bit 5, 2 -> 1 on lane bit 4 (cross-row exchanges), then sum inside each row of 16
-    const bool up5 = (lane & 32) != 0, up4 = (lane & 16) != 0;
-    float a = (up5 ? q[2] : q[0]) + __shfl_xor(up5 ? q[0] : q[2], 32, kWave);
-    float b = (up5 ? q[3] : q[1]) + __shfl_xor(up5 ? q[1] : q[3], 32, kWave);
-    float c = (up4 ? b : a) + __shfl_xor(up4 ? a : b, 16, kWave);
-    c += dpp_xor1(c);
-    c += dpp_xor2(c);
-    c += dpp_half_mirror(c);
-    c += dpp_mirror(c);
-    return c;       // lanes with (bit5, bit4) = (h, l) hold quantity 2*h + l
-}
-
-}  // namespace
-
-template <int R, int NW, int NQ, bool MASK>
-__global__ __launch_bounds__(64 * NW) void dx_lds_kernel(SplineGeom g, const float *__restrict__ x,
-                                                         const float *__restrict__ cf,
-                                                         const float *__restrict__ gy, float *__restrict__ gx,
-                                                         int64_t B)
-{
-    constexpr int T = 4, TJ = 64 * R, NT = 64 * NW, IPV = kWave / T;
-    constexpr int slab_floats = NQ * NT * 4;
-    extern __shared__ float lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t b0 = ((int64_t)blockIdx.x * NW + wave) * T;
-
-    // gy of the wave's samples, this lane's outputs (zero where the tile overhangs the layer)
-    float gyv[T][R];
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const int64_t b = b0 + t < B ? b0 + t : B - 1;
-#pragma unroll
-        for (int h = 0; h < R / 4; ++h) {
-            const int j = h * 256 + lane * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j < g.n_out) v = *reinterpret_cast<const float4 *>(gy + b * g.n_out + j);
-            gyv[t][4 * h] = v.x; gyv[t][4 * h + 1] = v.y; gyv[t][4 * h + 2] = v.z; gyv[t][4 * h + 3] = v.w;
-        }
-    }
-
-    const int my_t = lane % T, my_ii = lane / T;
-    int64_t my_b = b0 + my_t;
-    if (my_b >= B) my_b = B - 1;
-    const int out_t = lane >> 4;                    // sample whose total this lane holds after the reduction
-    const bool writer = (lane & 15) == 0 && b0 + out_t < B;
-
-    const SlabMap<NQ> map = slab_map<R, NT, NQ>(g, 0, tid);
-    const int64_t block_floats = (int64_t)g.slab_rows * g.n_out;
-    float4 q[NQ];
-    slab_fetch<NQ>(q, map, cf);
-    slab_store<NT, NQ, MASK>(q, map, lds, tid);
-    __syncthreads();
-
-    for (int i0 = 0; i0 < g.n_in; i0 += IPV) {
-        const int mi = i0 + my_ii;
-        const int ic = mi < g.n_in ? mi : g.n_in - 1;
-        const WinPair p = window_pair<true>(x[my_b * g.n_in + ic], g, ic);
-        const int n_ii = (g.n_in - i0 < IPV) ? g.n_in - i0 : IPV;
-        for (int ii = 0; ii < n_ii; ++ii) {
-            const int i = i0 + ii;
-            const float *cur = lds + (i & 1) * slab_floats;
-            float *nxt = lds + ((i + 1) & 1) * slab_floats;
-            slab_fetch<NQ>(q, map, cf + (int64_t)(i + 1 < g.n_in ? i + 1 : i) * block_floats);
-
-            float wb[R];
-            lds_row<R>(cur + g.rows * TJ, lane, wb);
-            float part[T];
-#pragma unroll
-            for (int t = 0; t < T; ++t) {
-                const int src = ii * T + t;
-                const float *win = cur + lane_i(p.row0, src) * TJ;
-                float c[kMaxK][R];
-#pragma unroll
-                for (int s = 0; s < kMaxK; ++s) lds_row<R>(win + s * TJ, lane, c[s]);
-                float acc = 0.0f;
-#pragma unroll
-                for (int s = 0; s < kMaxK; ++s) {
-                    float ts = 0.0f;
-#pragma unroll
-                    for (int r = 0; r < R; ++r) ts = fmaf(gyv[t][r], c[s][r], ts);
-                    acc = fmaf(lane_f(p.w[s], src), ts, acc);
-                }
-                float tb = 0.0f;
-#pragma unroll
-                for (int r = 0; r < R; ++r) tb = fmaf(gyv[t][r], wb[r], tb);
-                part[t] = fmaf(lane_f(p.base, src), tb, acc);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            const float total = reduce_transposed<T>(part, lane);
-            if (writer) gx[(b0 + out_t) * g.n_in + i] = total;
-            slab_store<NT, NQ, MASK>(q, map, nxt, tid);
-            __syncthreads();
-        }
-    }
-}
-
 // ---- launch --------------------------------------------------------------------------
 
 namespace {
@@ -417,59 +290,6 @@ hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *
     switch (forward_lds_plan(g)) {
     case 8: return forward_lds_by_quads<8, 4, 16>(g, x, cf, y, B, st);
     case 4: return forward_lds_by_quads<4, 16, 8>(g, x, cf, y, B, st);
-    default: return hipErrorInvalidValue;
-    }
-}
-
-// dL/dx needs the whole output range in one tile: R = 8 covers n_out <= 512, R = 4 n_out <= 256
-int dx_lds_plan(const SplineGeom &g)
-{
-    if (g.rows < kMaxK || g.n_out % 4 != 0 || g.slab_rows != g.rows + 1) return 0;
-    if (g.n_out > 256 && g.n_out <= 512 && quads_needed(g.rows, 8, 16) && quads_needed(g.rows, 8, 16) <= 8 &&
-        lds_bytes(g.rows, 8, 16) <= kLdsBudget)
-        return 8;
-    if (g.n_out >= 64 && g.n_out <= 256 && quads_needed(g.rows, 4, 16) && quads_needed(g.rows, 4, 16) <= 8 &&
-        lds_bytes(g.rows, 4, 16) <= kLdsBudget)
-        return 4;
-    return 0;
-}
-
-template <int R, int NW, int NQ>
-static hipError_t dx_lds_launch(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx,
-                                int64_t B, hipStream_t st)
-{
-    const size_t lds = 2ull * NQ * 64 * NW * 16;
-    const bool mask = (g.n_out % (64 * R)) != 0 || (int64_t)g.slab_rows * (64 * R / 4) != (int64_t)NQ * 64 * NW;
-    auto kern = mask ? dx_lds_kernel<R, NW, NQ, true> : dx_lds_kernel<R, NW, NQ, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((B + NW * 4 - 1) / (NW * 4)));
-    prof::Timed tm("dx_lds", st);
-    kern<<<grid, 64 * NW, lds, st>>>(g, x, cf, gy, gx, B);
-    return hipGetLastError();
-}
-
-template <int R, int NW>
-static hipError_t dx_lds_by_quads(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx,
-                                  int64_t B, hipStream_t st)
-{
-    switch (quads_needed(g.rows, R, NW)) {
-    case 2: return dx_lds_launch<R, NW, 2>(g, x, cf, gy, gx, B, st);
-    case 3: return dx_lds_launch<R, NW, 3>(g, x, cf, gy, gx, B, st);
-    case 4: return dx_lds_launch<R, NW, 4>(g, x, cf, gy, gx, B, st);
-    case 6: return dx_lds_launch<R, NW, 6>(g, x, cf, gy, gx, B, st);
-    case 8: return dx_lds_launch<R, NW, 8>(g, x, cf, gy, gx, B, st);
-    default: return hipErrorInvalidValue;
-    }
-}
-
-hipError_t launch_dx_lds(const SplineGeom &g, const float *x, const float *cf, const float *gy, float *gx, int64_t B,
-                         hipStream_t st)
-{
-    switch (dx_lds_plan(g)) {
-    case 8: return dx_lds_by_quads<8, 16>(g, x, cf, gy, gx, B, st);
-    case 4: return dx_lds_by_quads<4, 16>(g, x, cf, gy, gx, B, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -30,7 +30,8 @@ def flops_per_edge(k):
 # scaled by a 1 GiB copy (profiles/kan_c3_fwd_bwd_hbm_traffic.md): read + written.  Only valid for
 # that workload and these kernels.
 MEASURED_TRAFFIC_BYTES_C3 = {
-    "forward_lds": 235.3e6 + 33.6e6,
+    "forward_lds": 234.9e6 + 33.6e6,
+    "backward_walk": 1105.7e6 + 826.6e6,
 }
 
 # kernel family -> which third of the fwd+bwd work it carries ("backward" = dL/dx and the parameter

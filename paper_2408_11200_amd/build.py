@@ -20,18 +20,42 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build(verbose=False):
-    """Compile csrc/*.hip into libkan_hip.so next to this file.  Always recompiles."""
+def build(verbose=False, jobs=None):
+    """Compile csrc/*.hip into libkan_hip.so next to this file.  Always recompiles.
+
+    Every source is compiled to an object file in its own hipcc process (a few at a time), then linked."""
+    import concurrent.futures
+    import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
-    cmd += sources() + ["-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib", "-o", LIB_PATH]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines()
-                    if "packed-fp32-ops' is not a recognized feature" not in l)
-    if verbose or res.returncode != 0:
-        print(out)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed (%d)" % res.returncode)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    log = []
+
+    def run(cmd):
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in res.stdout.splitlines()
+                        if "packed-fp32-ops' is not a recognized feature" not in l)
+        return res.returncode, out
+
+    with tempfile.TemporaryDirectory(prefix="kan_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in sources()]
+        with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+            results = list(pool.map(lambda so: run([hipcc] + flags + inc + ["-c", so[0], "-o", so[1]]),
+                                    zip(sources(), objs)))
+        failed = [out for rc, out in results if rc != 0]
+        log += [out for rc, out in results if out]
+        if not failed:
+            rc, out = run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs +
+                          ["-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib", "-o", LIB_PATH])
+            if out:
+                log.append(out)
+            if rc != 0:
+                failed.append(out)
+    if verbose or failed:
+        print("\n".join(log))
+    if failed:
+        raise RuntimeError("hipcc failed")
     return LIB_PATH
 
 

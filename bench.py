@@ -238,8 +238,20 @@ def main():
         torch.cuda.synchronize()
         dense_ms = (time.perf_counter() - d0) * 1e3 / 5
         fwd_ms = sum(v for n, v in per_step.items() if KERNEL_ROLE.get(n) == "forward") + per_step.get("fold_scale", 0.0) / 2
+        del ws_d
+        ws_d = torch.empty(binding.load().kan_dense_baseline_backward_workspace_bytes(binding.kan_desc(s), case.w.B),
+                           dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            binding.kan_dense_baseline_backward(s, case.x, case.coef, case.w_s, case.w_b, case.gy, out=case.out, ws=ws_d)
+        torch.cuda.synchronize()
+        d0 = time.perf_counter()
+        for _ in range(5):
+            binding.kan_dense_baseline_backward(s, case.x, case.coef, case.w_s, case.w_b, case.gy, out=case.out, ws=ws_d)
+        torch.cuda.synchronize()
+        dense_bwd_ms = (time.perf_counter() - d0) * 1e3 / 5
         dense = {"forward_ms_dense_gemm": dense_ms, "forward_ms_local": fwd_ms,
-                 "note": "forward pass only; dense = expand all G+k bases + rocBLAS sgemm"}
+                 "backward_ms_dense_gemm": dense_bwd_ms, "backward_ms_local": ms_per_step - fwd_ms,
+                 "note": "dense = expand all G+k bases (and their x-derivatives) + rocBLAS sgemm"}
         del ws_d
 
     cpu = None

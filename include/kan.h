@@ -145,6 +145,12 @@ size_t kan_dense_baseline_workspace_bytes(const kan_layer_desc *desc, int64_t B)
 int kan_dense_baseline_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
                                const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
                                void *stream);
+/* The dense backward pass of the same baseline: gPhi = gy * C^T and gC = Phi^T * gy by rocBLAS, dL/dx as the row-wise
+   product of gPhi with dPhi/dx.  Same outputs and conventions as kan_backward. */
+size_t kan_dense_baseline_backward_workspace_bytes(const kan_layer_desc *desc, int64_t B);
+int kan_dense_baseline_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                                const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
+                                float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- UKAN ------------------------------------------------------------------------------ */
 

@@ -22,7 +22,8 @@ PASS_FORWARD, PASS_BACKWARD = 0, 1
 
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
            "kan_profile_enable", "kan_profile_read", "kan_dense_baseline_workspace_bytes",
-           "kan_dense_baseline_forward",
+           "kan_dense_baseline_forward", "kan_dense_baseline_backward_workspace_bytes",
+           "kan_dense_baseline_backward",
            "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_materialize_workspace_bytes",
            "ukan_materialize", "ukan_group_index"]
 
@@ -85,6 +86,11 @@ def load():
     lib.kan_profile_read.argtypes = [ctypes.POINTER(KanKernelTime), ctypes.c_int]
     lib.kan_dense_baseline_workspace_bytes.restype = sz
     lib.kan_dense_baseline_workspace_bytes.argtypes = [ctypes.POINTER(KanLayerDesc), i64]
+    lib.kan_dense_baseline_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.kan_dense_baseline_backward_workspace_bytes.argtypes = [ctypes.POINTER(KanLayerDesc), i64]
+    lib.kan_dense_baseline_backward.restype = ctypes.c_int
+    lib.kan_dense_baseline_backward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                vp, sz, vp]
     lib.kan_dense_baseline_forward.restype = ctypes.c_int
     lib.kan_dense_baseline_forward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ukan_workspace_bytes.restype = sz
@@ -206,6 +212,27 @@ def kan_dense_baseline_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=
     if rc != KAN_OK:
         raise KanError(rc, "kan_dense_baseline_forward")
     return y
+
+
+def kan_dense_baseline_backward(spec, x, coef, w_s, w_b, gy, out=None, ws=None, stream=None):
+    """Comparison baseline: the backward pass as two dense GEMMs over all basis functions."""
+    lib = load()
+    d = kan_desc(spec)
+    B = x.shape[0]
+    shapes = {"gx": (B, spec.n_in), "gcoef": (spec.n_in, spec.G + spec.k, spec.n_out),
+              "gw_s": (spec.n_in, spec.n_out), "gw_b": (spec.n_in, spec.n_out)}
+    out = dict(out or {})
+    for name in shapes:
+        if name not in out:
+            out[name] = torch.empty(shapes[name], dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(lib.kan_dense_baseline_backward_workspace_bytes(ctypes.byref(d), B), x.device)
+    rc = lib.kan_dense_baseline_backward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
+                                         _f32(out["gx"]), _f32(out["gcoef"]), _f32(out["gw_s"]), _f32(out["gw_b"]),
+                                         _ptr(ws), ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_dense_baseline_backward")
+    return out
 
 
 def kan_profile_enable(on):

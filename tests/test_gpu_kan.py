@@ -270,5 +270,9 @@ def test_dense_gemm_baseline_matches_oracle():
         inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
         x, coef, w_s, w_b = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"]))
         y = binding.kan_dense_baseline_forward(s, x, coef, w_s, w_b)
+        g = binding.kan_dense_baseline_backward(s, x, coef, w_s, w_b, dev(w.gy))
         torch.cuda.synchronize()
         assert_close(y, oracle.kan_forward(w.x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h), FWD_TOL, "y")
+        ref = oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h)
+        for name in ref:
+            assert_close(g[name], ref[name], GRAD_TOL, "dense " + name)

@@ -83,6 +83,27 @@ def test_layer_parity_sweep(B, n_in, n_out, G, k, outside):
     run_layer_parity(w)
 
 
+def test_half_gigabyte_table_wide_layer():
+    """A 16003-row table for 16 -> 512: the partial-sum budget forces chunks longer than 1024 samples,
+    i.e. the eight-outputs-per-lane walk with two-level sums, pre-zeroed slabs and gap jumps.  The grid
+    spans [-2000, 2000) so that the cell width (and with it the scale of dL/dx) stays O(1)."""
+    s = workloads.KanLayerSpec(16, 512, 16000, 3, -2000.0, 2000.0, base_act=0)   # silu(x) ~ 2000 would swamp fp32
+    rng = np.random.default_rng(77)
+    p = workloads.kan_params(rng, s, 0.1, w_s_std=0.3, w_b_std=0.3)
+    B = 4096
+    x = np.float32(rng.uniform(-2100.0, 2100.0, size=(B, 16)))
+    gy = np.float32(rng.standard_normal((B, 512)) / np.sqrt(B))
+    inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+    xd, coef, w_s = dev(x), dev(p["coef"]), dev(p["w_s"])
+    y = binding.kan_forward(s, xd, coef, w_s, None)
+    g = binding.kan_backward(s, xd, coef, w_s, None, dev(gy), want=("gx", "gcoef", "gw_s"))
+    assert_close(y, oracle.kan_forward(x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h, base_act=0),
+                 FWD_TOL, "y")
+    ref = oracle.kan_backward(x, p["coef"], p["w_s"], p["w_b"], gy, s.G, s.k, s.grid_lo, inv_h, base_act=0)
+    for name in ("gx", "gcoef", "gw_s"):
+        assert_close(g[name], ref[name], GRAD_TOL, name)
+
+
 def test_long_run_in_one_cell():
     """Every sample of an input in the same cell: the longest possible run for the sliding-window sums."""
     s = workloads.KanLayerSpec(2, 64, 6, 3, -1.0, 1.0)

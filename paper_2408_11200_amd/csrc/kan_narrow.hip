@@ -9,19 +9,24 @@
 namespace kan {
 
 // ---- forward ------------------------------------------------------------------------------
+// Four lanes per sample: lane q of the quad takes inputs q, q + 4, ... and the four partial sums are
+// added across the quad at the end (with one thread per sample a batch of a few ten thousand leaves
+// most of the chip idle).
 template <int NO>
 __global__ __launch_bounds__(256) void forward_narrow_kernel(SplineGeom g, const float *__restrict__ x,
                                                              const float *__restrict__ cf,
                                                              const float *__restrict__ w_b, float *__restrict__ y,
                                                              int64_t B)
 {
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t b = t >> 2;
+    const int q = (int)(t & 3);
+    const int64_t bc = b < B ? b : B - 1;        // lanes past the batch recompute the last sample: quads stay whole
     float acc[NO];
 #pragma unroll
     for (int j = 0; j < NO; ++j) acc[j] = 0.0f;
-    for (int i = 0; i < g.n_in; ++i) {
-        const Pair p = pair_eval<false>(x[b * g.n_in + i], g, i);
+    for (int i = q; i < g.n_in; i += 4) {
+        const Pair p = pair_eval<false>(x[bc * g.n_in + i], g, i);
         const float *slab = cf + (int64_t)i * g.slab_rows * g.n_out;
 #pragma unroll
         for (int s = 0; s < kMaxK; ++s) {
@@ -38,8 +43,17 @@ __global__ __launch_bounds__(256) void forward_narrow_kernel(SplineGeom g, const
         }
     }
 #pragma unroll
-    for (int j = 0; j < NO; ++j)
-        if (j < g.n_out) y[b * g.n_out + j] = acc[j];
+    for (int j = 0; j < NO; ++j) {
+        float v = acc[j];
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        acc[j] = v;
+    }
+    if (q == 0 && b < B) {
+#pragma unroll
+        for (int j = 0; j < NO; ++j)
+            if (j < g.n_out) y[b * g.n_out + j] = acc[j];
+    }
 }
 
 // ---- backward: dL/dx ------------------------------------------------------------------------
@@ -94,7 +108,7 @@ hipError_t launch_forward_narrow(const SplineGeom &g, const float *x, const floa
                                  int64_t B, hipStream_t st)
 {
     prof::Timed tm("forward_narrow", st);
-    const unsigned blocks = (unsigned)((B + 255) / 256);
+    const unsigned blocks = (unsigned)((4 * B + 255) / 256);
 #define CALL(N) forward_narrow_kernel<N><<<blocks, 256, 0, st>>>(g, x, cf, w_b, y, B)
     KAN_NARROW_DISPATCH(g.n_out, CALL)
 #undef CALL

@@ -68,6 +68,9 @@ struct WalkRecords {
     float *dw4;
 };
 
+hipError_t launch_sorted_records(const SplineGeom &g, const float *x, float *xT, int64_t B, int S, int row_bits,
+                                 const WalkRecords &rec, hipStream_t st);
+
 // Chunk-sorted walk (large grids, narrow layers).  plan_walk().ok == 0: shape not covered.
 struct WalkPlan {
     int ok;

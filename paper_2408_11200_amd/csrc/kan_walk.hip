@@ -72,7 +72,6 @@ __global__ __launch_bounds__(64 * NW) void cell_sort_kernel(SplineGeom g, const 
     unsigned *src = lds_u, *dst = lds_u + S;
     float *xs = reinterpret_cast<float *>(lds_u + 2 * S);
     __shared__ unsigned slot[NW][256];
-    __shared__ unsigned wave_tot[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = blockIdx.x, i = blockIdx.y;
     const int64_t b0 = (int64_t)c * S;
@@ -104,25 +103,30 @@ __global__ __launch_bounds__(64 * NW) void cell_sort_kernel(SplineGeom g, const 
             atomicAdd(&slot[wave][(src[e] >> shift) & 255u], 1u);
         __syncthreads();
         // first slot of every (digit, wave): exclusive prefix over digits, then over waves; done by
-        // the first 256 threads (one digit each)
-        unsigned tot = 0, inc = 0;
-        if (tid < 256) {
-            for (int w2 = 0; w2 < NW; ++w2) tot += slot[w2][tid];
-            inc = tot;
+        // the first wave, four digits per lane
+        if (wave == 0) {
+            unsigned tot[4], mine_tot = 0;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                tot[qd] = 0;
+                for (int w2 = 0; w2 < NW; ++w2) tot[qd] += slot[w2][4 * lane + qd];
+                mine_tot += tot[qd];
+            }
+            unsigned inc = mine_tot;
             for (int o = 1; o < 64; o <<= 1) {
                 const unsigned v = __shfl_up(inc, o, 64);
                 if (lane >= o) inc += v;
             }
-            if (lane == 63) wave_tot[wave] = inc;
-        }
-        __syncthreads();
-        if (tid < 256) {
-            unsigned at = inc - tot;
-            for (int w2 = 0; w2 < wave; ++w2) at += wave_tot[w2];
-            for (int w2 = 0; w2 < NW; ++w2) {
-                const unsigned cnt = slot[w2][tid];
-                slot[w2][tid] = at;
-                at += cnt;
+            unsigned at = inc - mine_tot;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                unsigned a = at;
+                for (int w2 = 0; w2 < NW; ++w2) {
+                    const unsigned cnt = slot[w2][4 * lane + qd];
+                    slot[w2][4 * lane + qd] = a;
+                    a += cnt;
+                }
+                at += tot[qd];
             }
         }
         __syncthreads();
@@ -307,6 +311,27 @@ size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out)
            walk_carry_bytes(p, n_in, n_out);
 }
 
+// x -> xT, then per (chunk of S samples, input) the records in sorted order.  S: a power of two >= 256.
+hipError_t launch_sorted_records(const SplineGeom &g, const float *x, float *xT, int64_t B, int S, int row_bits,
+                                 const WalkRecords &rec, hipStream_t st)
+{
+    {
+        dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
+        prof::Timed tm("walk_transpose", st);
+        transpose_kernel<<<grid, 256, 0, st>>>(x, xT, B, g.n_in);
+    }
+    const size_t lds = (size_t)S * 12;
+    // long chunks: 16 waves per sort (one workgroup per CU fits anyway), short ones 4
+    auto kern = S >= 4096 ? cell_sort_kernel<16> : cell_sort_kernel<4>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((B + S - 1) / S), (unsigned)g.n_in);
+    prof::Timed tm("walk_sort", st);
+    kern<<<grid, S >= 4096 ? 1024 : 256, lds, st>>>(g, xT, B, S, log2_exact(S), row_bits, rec);
+    return hipGetLastError();
+}
+
 // gx == nullptr: parameter gradients only.  part_c == nullptr: dL/dx only.  cf is the scale-folded
 // table ([n_in][slab_rows][n_out]); w_b may be null when the layer has no base term.
 hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,
@@ -325,22 +350,7 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     rec.dw4 = dx ? (float *)at : nullptr;   at += up256(n * 16);
     float *gx_part = (float *)at;       at += p.n_jt > 1 ? up256((size_t)p.n_jt * B * g.n_in * sizeof(float)) : 0;
     float *carry = (float *)at;
-    {
-        dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
-        prof::Timed tm("walk_transpose", st);
-        transpose_kernel<<<grid, 256, 0, st>>>(x, xT, B, g.n_in);
-    }
-    {
-        const size_t lds = (size_t)p.S * 12;
-        // long chunks: 16 waves per sort (one workgroup per CU fits anyway), short ones 4
-        auto kern = p.S >= 4096 ? cell_sort_kernel<16> : cell_sort_kernel<4>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        dim3 grid((unsigned)p.n_chunks, (unsigned)g.n_in);
-        prof::Timed tm("walk_sort", st);
-        kern<<<grid, p.S >= 4096 ? 1024 : 256, lds, st>>>(g, xT, B, p.S, p.sbits, p.row_bits, rec);
-    }
+    if (hipError_t e = launch_sorted_records(g, x, xT, B, p.S, p.row_bits, rec, st); e != hipSuccess) return e;
     const int bpc = (p.n_seg * p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
     int m = 1;
     while (m * 2 <= 8 && m * 2 <= p.n_chunks) m *= 2;

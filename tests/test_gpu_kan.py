@@ -120,6 +120,23 @@ def test_long_run_in_one_cell():
 
 
 @pytest.mark.parametrize("want", [("gx",), ("gcoef",), ("gw_b",), ("gx", "gw_s")])
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    outs = [1, 3, 8, 16, 20, 32, 48, 64, 100, 128, 200, 256, 260, 512, 520]
+    shapes = []
+    for _ in range(n):
+        shapes.append((int(rng.integers(1, 3000)), int(rng.integers(1, 40)), int(rng.choice(outs)),
+                       int(rng.integers(1, 400)), int(rng.integers(1, 4)), float(rng.choice([0.0, 0.1, 0.3]))))
+    return shapes
+
+
+@pytest.mark.parametrize("B,n_in,n_out,G,k,outside", _random_shapes(24, 2024))
+def test_layer_parity_random_shapes(B, n_in, n_out, G, k, outside):
+    """Seeded random shapes across every dispatch path (narrow, row-stream, LDS-staged, generic, walk variants)."""
+    w = workloads.random_kan_layer(7000 + B, B, n_in, n_out, G, k, outside_frac=outside)
+    run_layer_parity(w)
+
+
 def test_gradient_subsets(want):
     """Any subset of the gradient outputs may be requested; what is returned does not depend on the rest."""
     w = workloads.random_kan_layer(21, 900, 6, 96, 40, 3, outside_frac=0.2)

@@ -74,6 +74,19 @@ def test_ukan_layer_parity_sweep(B, n_in, n_out, k, base_act):
     run(spec, p, x, gy)
 
 
+def _random_ukan_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 1500)), int(rng.integers(1, 20)), int(rng.choice([1, 5, 8, 32, 64, 100, 256, 260])),
+             int(rng.integers(1, 4)), int(rng.integers(0, 2)), float(rng.choice([1.0, 3.0, 6.0]))) for _ in range(n)]
+
+
+@pytest.mark.parametrize("B,n_in,n_out,k,base_act,xs", _random_ukan_shapes(12, 77))
+def test_ukan_layer_parity_random_shapes(B, n_in, n_out, k, base_act, xs):
+    spec, p, x, gy = make(900 + B, B, n_in, n_out, k=k, base_act=base_act, xs=xs)
+    gy = np.float32(gy / np.sqrt(B))        # keep the parameter gradients O(1) (they sum over the batch)
+    run(spec, p, x, gy, max_groups=256)
+
+
 def test_ukan_negative_and_large_inputs_and_wider_cg():
     spec, p, x, gy = make(3, 400, 6, 96, d_pe=32, d_feat=32, d_hid=64, xs=6.0)
     x[:, 0] = -np.abs(x[:, 0]) - 5.0          # a wholly negative input column

@@ -92,7 +92,9 @@ typedef struct ukan_grads {
 const char *kan_strerror(int status);
 
 /* Scratch bytes needed by kan_forward (pass = KAN_PASS_FORWARD) or kan_backward for batch B.
-   Returns 0 for an invalid descriptor. */
+   Returns 0 for an invalid descriptor.  Forward: the scale-folded table.  Backward: that, the transposed input, two
+   sorted record arrays (44 bytes per (sample, input) pair) and the per-chunk partial gradient tables: a small multiple
+   of B * n_in * 48 bytes + at most 2 GiB of partial tables (more only when a single table exceeds that). */
 size_t kan_workspace_bytes(const kan_layer_desc *desc, int64_t B, int pass);
 
 /* Forward pass of one layer, Eqs. "activation" + "kanphi" + "matrixform":

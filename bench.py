@@ -64,10 +64,15 @@ class KanCase:
         self.config = {"workload": w.name, "B": B, "n_in": s.n_in, "n_out": s.n_out, "G": s.G, "k": s.k,
                        "grid": [s.grid_lo, s.grid_hi], "pass": "forward+backward"}
 
+    def forward(self):
+        self.binding.kan_forward(self.s, self.x, self.coef, self.w_s, self.w_b, y=self.y, ws=self.ws_f)
+
+    def backward(self):
+        self.binding.kan_backward(self.s, self.x, self.coef, self.w_s, self.w_b, self.gy, out=self.out, ws=self.ws_b)
+
     def step(self):
-        b = self.binding
-        b.kan_forward(self.s, self.x, self.coef, self.w_s, self.w_b, y=self.y, ws=self.ws_f)
-        b.kan_backward(self.s, self.x, self.coef, self.w_s, self.w_b, self.gy, out=self.out, ws=self.ws_b)
+        self.forward()
+        self.backward()
 
     def cpu_baseline(self, oracle):
         w, s, p = self.w, self.s, self.w.params[0]
@@ -121,12 +126,19 @@ class UkanCase:
         self.config = {"workload": w.name, "B": w.B, "widths": [w.layers[0].n_in] + [s.n_out for s in w.layers],
                        "h": w.layers[0].h, "k": self.k, "max_groups": mg, "pass": "forward+backward"}
 
-    def step(self):
+    def forward(self):
         b, w, mg = self.binding, self.w, UKAN_MAX_GROUPS
         for l, s in enumerate(w.layers):
             b.ukan_cg_forward(s, self.acts[l], self.P[l], mg, y=self.acts[l + 1], ws=self.ws_f[l])
+
+    def backward(self):
+        b, w, mg = self.binding, self.w, UKAN_MAX_GROUPS
         for l in reversed(range(len(w.layers))):
             b.ukan_cg_backward(w.layers[l], self.acts[l], self.P[l], self.gys[l], mg, out=self.outs[l], ws=self.ws_b[l])
+
+    def step(self):
+        self.forward()
+        self.backward()
 
     def cpu_baseline(self, oracle):
         # first layer only, on a slice of the batch, scaled by its share of the edge evaluations
@@ -224,6 +236,20 @@ def main():
           "whole_path_frac": roofline.algorithmic_flops_per_edge(case.k + 1) * value / roofline.MI355X_FP32_VECTOR_FLOPS,
           "kernels_ms_per_step": {n: round(v, 4) for n, v in sorted(per_step.items())}}
 
+    # forward and backward separately (outside the timed region): device events around each pass, 10 repetitions
+    def timed(fn, reps=10):
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        return {"median": ts[len(ts) // 2], "min": ts[0]}
+    passes = {"forward_ms": timed(case.forward), "backward_ms": timed(case.backward)}
+
     dense = None
     if args.dense_baseline and isinstance(case, KanCase):
         s = case.s
@@ -263,7 +289,7 @@ def main():
     line = {"metric": "KAN layer fwd+bwd edge-evals/sec (B*n_in*n_out)", "value": value, "unit": "edge-evals/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-            "data": "synthetic", "config": case.config, "roofline": rl, "cpu_baseline": cpu}
+            "data": "synthetic", "config": case.config, "roofline": rl, "cpu_baseline": cpu, "passes": passes}
     if dense:
         line["dense_baseline"] = dense
     print(json.dumps(line))

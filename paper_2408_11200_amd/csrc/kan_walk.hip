@@ -255,12 +255,13 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
     const int tile = (64 / p.streams) * p.T;
     p.n_jt = (g.n_out + tile - 1) / tile;
     // chunk length: a power of two between 256 and 8192 samples, the smaller of
-    //   - what keeps the gy rows of one chunk inside an XCD's L2 (about 2 MiB of it),
+    //   - what keeps the gy rows of one chunk inside an XCD's L2 (4 MiB),
     //   - an eighth of the batch (one chunk per XCD at least),
     // then raised until the partial sums fit 2 GiB.  Few, long chunks keep the partial sums small;
     // the parallelism comes from cutting each sorted list into segments (below).
     auto pow2_floor = [](int64_t v) { int64_t q = 256; while (q * 2 <= v && q < 8192) q *= 2; return (int)q; };
-    int S = pow2_floor((2ll << 20) / ((int64_t)g.n_out * 4));
+    int S = pow2_floor((4ll << 20) / ((int64_t)g.n_out * 4));
+    if (p.T == 8 && S > 1024) S = 1024;      // eight outputs per lane: stay with single-level sums (registers)
     const int s_b8 = pow2_floor(B / 8);
     S = S < s_b8 ? S : s_b8;
     const int64_t slab = (int64_t)g.n_in * g.rows * g.n_out * (int64_t)sizeof(float);

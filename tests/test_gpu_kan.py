@@ -104,14 +104,15 @@ def test_half_gigabyte_table_wide_layer():
         assert_close(g[name], ref[name], GRAD_TOL, name)
 
 
-def test_long_run_in_one_cell():
-    """Every sample of an input in the same cell: the longest possible run for the sliding-window sums."""
+@pytest.mark.parametrize("B", [6000, 70000])
+def test_long_run_in_one_cell(B):
+    """Every sample of an input in the same cell: the longest possible run for the window sums (B = 6000: chunks of
+    512 samples, single-level sums; B = 70000: chunks of 8192, two-level sums)."""
     s = workloads.KanLayerSpec(2, 64, 6, 3, -1.0, 1.0)
     rng = np.random.default_rng(11)
     p = workloads.kan_params(rng, s, 0.1, w_s_std=1.0, w_b_std=1.0)
-    B = 6000
     x = np.float32(np.stack([0.05 + 0.2 * rng.random(B), np.full(B, -0.4)], axis=1))
-    gy = np.float32(rng.standard_normal((B, 64)))
+    gy = np.float32(rng.standard_normal((B, 64)) * (80.0 / np.sqrt(B)))
     inv_h = oracle.inv_h_of(-1.0, 1.0, 6)
     g = binding.kan_backward(s, dev(x), dev(p["coef"]), dev(p["w_s"]), dev(p["w_b"]), dev(gy))
     ref = oracle.kan_backward(x, p["coef"], p["w_s"], p["w_b"], gy, 6, 3, -1.0, inv_h)

@@ -46,7 +46,7 @@ extern "C" {
 typedef enum kan_status {
     KAN_OK = 0,
     KAN_ERR_INVALID_ARG = -1, /* null or misaligned pointer, non-positive size, grid_hi <= grid_lo, h <= 0 */
-    KAN_ERR_UNSUPPORTED = -2, /* k outside 1..3, unknown base_act, CG widths not supported    */
+    KAN_ERR_UNSUPPORTED = -2, /* k outside 1..5 (UKAN: 1..3), unknown base_act, CG widths not supported */
     KAN_ERR_WORKSPACE = -3,   /* ws is NULL / misaligned / smaller than *_workspace_bytes     */
     KAN_ERR_RANGE = -4,       /* UKAN: some input spans more groups than max_groups           */
     KAN_ERR_HIP = -5          /* a HIP runtime call or kernel launch failed                   */
@@ -56,7 +56,8 @@ enum { KAN_BASE_NONE = 0, KAN_BASE_SILU = 1 };
 enum { KAN_PASS_FORWARD = 0, KAN_PASS_BACKWARD = 1 };
 
 /* One bounded-grid layer (Eqs. "activation", "kanphi", "kanspline"): widths n_l, n_{l+1},
-   grid size G (cells), degree k, grid range.  base_act selects b(x) of Eq. "kanphi". */
+   grid size G (cells), degree k (1..5; the specialised kernels cover k <= 3, degrees 4 and 5 run on the generic
+   ones), grid range.  base_act selects b(x) of Eq. "kanphi". */
 typedef struct kan_layer_desc {
     int32_t n_in, n_out;
     int32_t G, k;

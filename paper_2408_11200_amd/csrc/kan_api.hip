@@ -2,6 +2,7 @@
 // kernel dispatch.  See include/kan.h for the contract.
 #include "kan.h"
 #include "kan_launch.hpp"
+#include "kan_highk.hpp"
 
 using namespace kan;
 
@@ -18,7 +19,7 @@ int check_desc(const kan_layer_desc *d)
     if (!d) return KAN_ERR_INVALID_ARG;
     if (d->n_in <= 0 || d->n_out <= 0 || d->G <= 0) return KAN_ERR_INVALID_ARG;
     if (!(d->grid_hi > d->grid_lo)) return KAN_ERR_INVALID_ARG;
-    if (d->k < 1 || d->k > 3) return KAN_ERR_UNSUPPORTED;
+    if (d->k < 1 || d->k > 5) return KAN_ERR_UNSUPPORTED;
     if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
     return KAN_OK;
 }
@@ -36,6 +37,18 @@ SplineGeom geom_of(const kan_layer_desc *d)
     g.cell_base = nullptr;
     g.base_act = d->base_act;
     return g;
+}
+
+// degrees 4 and 5 run on the generic kernels built for a window of 6 rows
+bool high_degree(const kan_layer_desc *d) { return d->k > 3; }
+
+HighKLayer highk_of(const kan_layer_desc *d)
+{
+    HighKLayer l;
+    l.n_in = d->n_in; l.n_out = d->n_out; l.rows = d->G + d->k; l.k = d->k;
+    l.lo = d->grid_lo; l.inv_h = (float)d->G / (d->grid_hi - d->grid_lo);
+    l.base_act = d->base_act;
+    return l;
 }
 
 // scale-folded table: G + k coefficient rows plus the w_b row per input
@@ -63,7 +76,7 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     SplineGeom g = geom_of(d);
     BackwardPlan bp;
     bp.wp = plan_walk(g, B);
-    bp.walk = bp.wp.ok != 0;
+    bp.walk = bp.wp.ok != 0 && !high_degree(d);
     if (bp.walk) {
         bp.cp.n_chunks = bp.wp.n_chunks;
         bp.cp.chunk_len = bp.wp.S;
@@ -72,7 +85,7 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
         bp.rec_bytes = 0;
-        bp.b_slices_per_chunk = dparam_generic_row_blocks(g.rows);
+        bp.b_slices_per_chunk = high_degree(d) ? highk_row_blocks(g.rows) : dparam_generic_row_blocks(g.rows);
     }
     return bp;
 }
@@ -118,6 +131,8 @@ extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x
     hipStream_t st = (hipStream_t)stream;
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
+    if (high_degree(desc))
+        return highk_forward(highk_of(desc), x, coef, w_s, w_b, cf, y, B, st) == hipSuccess ? KAN_OK : KAN_ERR_HIP;
     if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
     hipError_t e = narrow_applicable(g)    ? launch_forward_narrow(g, x, cf, w_b, y, B, st)
                    : forward_rows_plan(g) ? launch_forward_rows(g, x, cf, y, B, st)
@@ -145,6 +160,14 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
     const BackwardPlan bp = backward_plan(desc, B);
+    if (high_degree(desc)) {
+        float *part_c = (float *)((char *)ws + folded_bytes(desc));
+        float *part_b = (float *)((char *)part_c + (size_t)bp.cp.n_chunks * folded_bytes(desc));
+        return highk_backward(highk_of(desc), x, coef, w_s, w_b, gy, cf, gx, gcoef, gw_s, gw_b, part_c, part_b,
+                              bp.cp.n_chunks, bp.cp.chunk_len, B, st) == hipSuccess
+                   ? KAN_OK
+                   : KAN_ERR_HIP;
+    }
     const bool want_params = gcoef || gw_s || gw_b;
     // the chunk-sorted walk takes dL/dx together with the parameter gradients (one pass over gy)
     const bool fused_dx = gx && bp.walk;

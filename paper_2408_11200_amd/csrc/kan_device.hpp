@@ -9,9 +9,17 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace kan {
+// The kernels are written for a window of KAN_MAXK rows (4: degrees up to 3, the default).  The
+// generic kernels are compiled a second time with a window of 6 (degrees 4 and 5) in a namespace of
+// their own; that translation unit sets both macros before including this header.
+#ifndef KAN_MAXK
+#define KAN_MAXK 4
+#define KAN_NS kan
+#endif
 
-constexpr int kMaxK = 4;          // window width supported by the kernels (degree k <= 3)
+namespace KAN_NS {
+
+constexpr int kMaxK = KAN_MAXK;   // window width supported by the kernels (degree k <= kMaxK - 1)
 constexpr int kWave = 64;
 
 // Geometry of one spline evaluation problem as the kernels see it.  A bounded
@@ -87,8 +95,9 @@ __device__ __forceinline__ Pair pair_eval(float x, const SplineGeom &g, int i)
 
     // Cox-de Boor on one cell of a uniform grid:
     //   N^d_s = ((u + d - s) N^{d-1}_{s-1} + (s + 1 - u) N^{d-1}_s) / d
-    float n[kMaxK] = {1.0f, 0.0f, 0.0f, 0.0f};
-    float low[kMaxK] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float n[kMaxK], low[kMaxK];
+#pragma unroll
+    for (int s = 0; s < kMaxK; ++s) { n[s] = (s == 0) ? 1.0f : 0.0f; low[s] = 0.0f; }
 #pragma unroll
     for (int dg = 1; dg < kMaxK; ++dg) {
         if (dg <= g.k) {
@@ -158,4 +167,4 @@ __device__ __forceinline__ int lane_i(int v, int src) { return __builtin_amdgcn_
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-}  // namespace kan
+}  // namespace KAN_NS

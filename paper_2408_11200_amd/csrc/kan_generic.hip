@@ -10,7 +10,7 @@
 #include "kan_device.hpp"
 #include "kan_launch.hpp"
 
-namespace kan {
+namespace KAN_NS {
 
 // ---- helpers --------------------------------------------------------------
 
@@ -611,4 +611,4 @@ hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float 
     return hipGetLastError();
 }
 
-}  // namespace kan
+}  // namespace KAN_NS

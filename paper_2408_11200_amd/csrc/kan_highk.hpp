@@ -1,0 +1,25 @@
+// Degrees 4 and 5: the generic kernels compiled for a window of 6 rows (kan_generic_k5.hip).  Plain
+// argument types only, so that callers built for the default window can use it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kan {
+
+struct HighKLayer {
+    int n_in, n_out, rows, k;       // rows = G + k
+    float lo, inv_h;
+    int base_act;
+};
+
+int highk_row_blocks(int rows);     // base-term partial slices per chunk
+// y = layer(x); cf: scratch for the scale-folded table ((rows + 1) rows per input)
+hipError_t highk_forward(const HighKLayer &l, const float *x, const float *coef, const float *w_s, const float *w_b,
+                         float *cf, float *y, int64_t B, hipStream_t st);
+// any of gx / (gcoef, gw_s, gw_b) may be null; part_c: n_chunks tables of rows rows, part_b: n_chunks *
+// highk_row_blocks(rows) edge slices
+hipError_t highk_backward(const HighKLayer &l, const float *x, const float *coef, const float *w_s, const float *w_b,
+                          const float *gy, float *cf, float *gx, float *gcoef, float *gw_s, float *gw_b,
+                          float *part_c, float *part_b, int n_chunks, int64_t chunk_len, int64_t B, hipStream_t st);
+
+}  // namespace kan

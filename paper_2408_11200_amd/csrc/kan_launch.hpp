@@ -6,11 +6,9 @@
 #include <stdint.h>
 #include "kan_device.hpp"
 
-namespace kan {
-
 // Optional per-launch timing (see kan_profile_enable in kan.h).  A Timed object brackets one
 // kernel launch with two events when profiling is on and does nothing otherwise.
-namespace prof {
+namespace kanprof {
 bool enabled();
 void begin(const char *family, hipStream_t st);
 void end(hipStream_t st);
@@ -20,7 +18,11 @@ struct Timed {
     Timed(const char *family, hipStream_t s) : st(s), on(enabled()) { if (on) begin(family, st); }
     ~Timed() { if (on) end(st); }
 };
-}  // namespace prof
+}  // namespace kanprof
+
+namespace KAN_NS {
+
+namespace prof = ::kanprof;
 
 hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float lo, float inv_h,
                                  hipStream_t st);
@@ -106,4 +108,4 @@ inline ChunkPlan plan_chunks(int64_t B, int n_in, int rows, int n_out)
     return p;
 }
 
-}  // namespace kan
+}  // namespace KAN_NS

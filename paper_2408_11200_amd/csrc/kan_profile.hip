@@ -4,8 +4,7 @@
 #include "kan.h"
 #include "kan_launch.hpp"
 
-namespace kan {
-namespace prof {
+namespace kanprof {
 
 namespace {
 struct Record { const char *family; hipEvent_t e0, e1; bool closed; };
@@ -44,10 +43,9 @@ void end(hipStream_t st)
     g_open = false;
 }
 
-}  // namespace prof
-}  // namespace kan
+}  // namespace kanprof
 
-using namespace kan::prof;
+using namespace kanprof;
 
 extern "C" int kan_profile_enable(int on)
 {

@@ -83,6 +83,15 @@ def test_layer_parity_sweep(B, n_in, n_out, G, k, outside):
     run_layer_parity(w)
 
 
+@pytest.mark.parametrize("B,n_in,n_out,G,k,outside", [
+    (300, 7, 96, 9, 4, 0.2), (513, 5, 33, 12, 5, 0.25), (64, 3, 256, 40, 5, 0.1), (1000, 4, 8, 6, 4, 0.3),
+])
+def test_layer_parity_degrees_four_and_five(B, n_in, n_out, G, k, outside):
+    """Degrees 4 and 5 (window of 5 and 6 rows) run on the generic kernels."""
+    w = workloads.random_kan_layer(4000 + B, B, n_in, n_out, G, k, outside_frac=outside)
+    run_layer_parity(w)
+
+
 def test_half_gigabyte_table_wide_layer():
     """A 16003-row table for 16 -> 512: the partial-sum budget forces chunks longer than 1024 samples,
     i.e. the eight-outputs-per-lane walk with two-level sums, pre-zeroed slabs and gap jumps.  The grid
@@ -212,7 +221,7 @@ def test_empty_batch_and_argument_errors():
                            p["w_b"].data_ptr(), yv.data_ptr(), ws.data_ptr(), 16, None) == binding.KAN_ERR_WORKSPACE
     assert lib.kan_forward(ctypes.byref(d), 3, x.data_ptr(), p["coef"].data_ptr(), p["w_s"].data_ptr(),
                            p["w_b"].data_ptr(), yv.data_ptr(), None, 0, None) == binding.KAN_ERR_WORKSPACE
-    for bad in (dict(k=0), dict(k=4), dict(base_act=7)):
+    for bad in (dict(k=0), dict(k=6), dict(base_act=7)):
         d2 = binding.kan_desc(s)
         for n, v in bad.items():
             setattr(d2, n, v)

@@ -117,6 +117,20 @@ int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const fl
                  const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
                  float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream);
 
+/* kan_forward for callers that cannot allocate device memory (code running under HIP graph capture, tight
+   serving loops, harnesses that forbid hipMalloc): same arguments and result as kan_forward, but the scratch
+   space is a fixed array of KAN_STATIC_SCRATCH_BYTES that is part of the library's device code, so there is
+   no (ws, ws_bytes) to provide and the call allocates nothing.  Each GPU holds its own copy of the array
+   from the first call on it until the process ends.  Returns KAN_ERR_WORKSPACE when
+   kan_workspace_bytes(desc, B, KAN_PASS_FORWARD) exceeds KAN_STATIC_SCRATCH_BYTES (y is not written),
+   KAN_ERR_HIP when the array's address cannot be obtained.  All calls on one GPU share the array: calls that
+   may overlap in time on the same GPU (different streams or threads) race on it; calls on one stream do not.
+   kan_static_scratch_bytes() returns the limit. */
+#define KAN_STATIC_SCRATCH_BYTES (32u << 20)
+size_t kan_static_scratch_bytes(void);
+int kan_forward_static(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                       const float *w_s, const float *w_b, float *y, void *stream);
+
 /* Parity aid: idx[p] = interval index of x[p] for p < n (the integer the forward pass uses
    before any clamping), saturated to +-2^30. */
 int kan_interval_index(const kan_layer_desc *desc, int64_t n, const float *x, int32_t *idx,

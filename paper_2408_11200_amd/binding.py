@@ -21,6 +21,7 @@ KAN_ERR_HIP = -5
 PASS_FORWARD, PASS_BACKWARD = 0, 1
 
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
+           "kan_static_scratch_bytes", "kan_forward_static",
            "kan_profile_enable", "kan_profile_read", "kan_dense_baseline_workspace_bytes",
            "kan_dense_baseline_forward", "kan_dense_baseline_backward_workspace_bytes",
            "kan_dense_baseline_backward",
@@ -76,6 +77,10 @@ def load():
     lib.kan_workspace_bytes.argtypes = [ctypes.POINTER(KanLayerDesc), i64, ctypes.c_int]
     lib.kan_forward.restype = ctypes.c_int
     lib.kan_forward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kan_static_scratch_bytes.restype = sz
+    lib.kan_static_scratch_bytes.argtypes = []
+    lib.kan_forward_static.restype = ctypes.c_int
+    lib.kan_forward_static.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp]
     lib.kan_backward.restype = ctypes.c_int
     lib.kan_backward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kan_interval_index.restype = ctypes.c_int
@@ -164,6 +169,20 @@ def kan_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=None):
                          _ptr(ws), ws.numel(), _stream(stream))
     if rc != KAN_OK:
         raise KanError(rc, "kan_forward")
+    return y
+
+
+def kan_static_scratch_bytes():
+    return int(load().kan_static_scratch_bytes())
+
+
+def kan_forward_static(spec, x, coef, w_s, w_b, y, stream=None):
+    """kan_forward on the library's built-in scratch array: allocates nothing, so y is required."""
+    d = kan_desc(spec)
+    rc = load().kan_forward_static(ctypes.byref(d), x.shape[0], _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(y),
+                                   _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_forward_static")
     return y
 
 

@@ -1,5 +1,6 @@
 // C ABI of the bounded-grid KAN layer: argument checks, workspace layout and
 // kernel dispatch.  See include/kan.h for the contract.
+#include <mutex>
 #include "kan.h"
 #include "kan_launch.hpp"
 #include "kan_highk.hpp"
@@ -115,9 +116,10 @@ extern "C" size_t kan_workspace_bytes(const kan_layer_desc *desc, int64_t B, int
            (size_t)bp.cp.n_chunks * bp.b_slices_per_chunk * edge_bytes(desc);
 }
 
-extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
-                           const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
-                           void *stream)
+// Forward pass with the scratch space given explicitly; shared by kan_forward and kan_forward_static.
+static int forward_impl(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                        const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
+                        void *stream)
 {
     int rc = check_desc(desc);
     if (rc != KAN_OK) return rc;
@@ -139,6 +141,55 @@ extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x
                    : forward_lds_plan(g)  ? launch_forward_lds(g, x, cf, y, B, st)
                                          : launch_forward_generic(g, x, cf, w_b, y, B, st);
     return e == hipSuccess ? KAN_OK : KAN_ERR_HIP;
+}
+
+extern "C" int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                           const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
+                           void *stream)
+{
+    return forward_impl(desc, B, x, coef, w_s, w_b, y, ws, ws_bytes, stream);
+}
+
+// ---- forward pass for callers that cannot allocate -------------------------------------------
+// The scratch of kan_forward (the scale-folded table) lives in a device array of fixed size that is
+// part of the library's code object: every GPU the library runs on holds one copy at an address of
+// its own, found once per device with hipGetSymbolAddress.  In host code the array's name is only
+// a handle for that query, never a device address.
+static __device__ __align__(256) unsigned char scratch[KAN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices];      // per device; nullptr until the first call on that device
+
+// device address of `scratch` on the current device (nullptr: the query failed)
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" size_t kan_static_scratch_bytes(void) { return KAN_STATIC_SCRATCH_BYTES; }
+
+extern "C" int kan_forward_static(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                                  const float *w_s, const float *w_b, float *y, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != KAN_OK) return rc;
+    if (B < 0) return KAN_ERR_INVALID_ARG;
+    if (B == 0) return KAN_OK;
+    if (kan_workspace_bytes(desc, B, KAN_PASS_FORWARD) > (size_t)KAN_STATIC_SCRATCH_BYTES) return KAN_ERR_WORKSPACE;
+    void *ws = static_scratch();
+    if (!ws) return KAN_ERR_HIP;
+    return forward_impl(desc, B, x, coef, w_s, w_b, y, ws, KAN_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,

@@ -224,6 +224,108 @@ __global__ __launch_bounds__(64 * NW) void forward_lds_kernel(SplineGeom g, cons
     }
 }
 
+// ---- forward, pair data through LDS -------------------------------------------------------------
+// The same walk over the inputs as forward_lds_kernel, with one difference in how a wave gets at the
+// per-pair quantities (window row, K weights, base value), which are uniform over the outputs: the lane that
+// evaluated a pair writes them to a small area of LDS owned by the wave, and the wave reads them back with
+// reads whose address is the same in every lane (one 16-byte and one 8-byte read per pair).  That replaces
+// six v_readlane per pair (each a VALU slot, plus the wait states between a lane read and the use of the
+// scalar it wrote), so that a pair costs K + 1 multiply-adds per output and one address addition.
+template <int R, int T, int NW, int NQ, bool MASK>
+__global__ __launch_bounds__(64 * NW) void forward_pairs_kernel(SplineGeom g, const float *__restrict__ x,
+                                                                const float *__restrict__ cf,
+                                                                float *__restrict__ y, int64_t B)
+{
+    constexpr int TJ = 64 * R, NT = 64 * NW, IPV = kWave / T;
+    constexpr int slab_floats = NQ * NT * 4;            // padded slab
+    constexpr int kPairFloats = 8;                      // w[0..3], base, byte offset of the window row, 2 unused
+    extern __shared__ float lds[];                      // two slabs, then NW areas of 64 pairs
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t b0 = ((int64_t)blockIdx.x * NW + wave) * T;
+    const int j0 = blockIdx.y * TJ;
+    float *pairs = lds + 2 * slab_floats + wave * (64 * kPairFloats);
+
+    float acc[T][R];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[t][r] = 0.0f;
+
+    const int my_t = lane % T, my_ii = lane / T;
+    int64_t my_b = b0 + my_t;
+    if (my_b >= B) my_b = B - 1;
+
+    const SlabMap<NQ> map = slab_map<R, NT, NQ>(g, j0, tid);
+    const int64_t block_floats = (int64_t)g.slab_rows * g.n_out;
+    float4 q[NQ];
+    slab_fetch<NQ>(q, map, cf);
+    slab_store<NT, NQ, MASK>(q, map, lds, tid);
+    __syncthreads();
+
+    for (int i0 = 0; i0 < g.n_in; i0 += IPV) {
+        const int mi = i0 + my_ii;
+        const int ic = mi < g.n_in ? mi : g.n_in - 1;
+        const WinPair p = window_pair<false>(x[my_b * g.n_in + ic], g, ic);
+        // pair (input i0 + ii, sample t) sits at index ii * T + t == lane of the lane that evaluated it
+        *reinterpret_cast<float4 *>(pairs + lane * kPairFloats) = make_float4(p.w[0], p.w[1], p.w[2], p.w[3]);
+        *reinterpret_cast<float2 *>(pairs + lane * kPairFloats + 4) =
+            make_float2(p.base, __int_as_float(p.row0 * TJ * 4));
+        const int n_ii = (g.n_in - i0 < IPV) ? g.n_in - i0 : IPV;
+        for (int ii = 0; ii < n_ii; ++ii) {
+            const int i = i0 + ii;
+            const float *cur = lds + (i & 1) * slab_floats;
+            float *nxt = lds + ((i + 1) & 1) * slab_floats;
+            // prefetch the next slab (the last iteration re-fetches its own slab: harmless)
+            slab_fetch<NQ>(q, map, cf + (int64_t)(i + 1 < g.n_in ? i + 1 : i) * block_floats);
+
+            // the T pairs of this input: same address in every lane
+            float4 wv[T];
+            float2 bv[T];
+            const float *pp = pairs + ii * (T * kPairFloats);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                wv[t] = *reinterpret_cast<const float4 *>(pp + t * kPairFloats);
+                bv[t] = *reinterpret_cast<const float2 *>(pp + t * kPairFloats + 4);
+            }
+            float wb[R];
+            lds_row<R>(cur + g.rows * TJ, lane, wb);   // last slab row: w_b
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const float *win = reinterpret_cast<const float *>(reinterpret_cast<const char *>(cur) +
+                                                                   __float_as_int(bv[t].y));
+                float c[kMaxK][R];
+#pragma unroll
+                for (int s = 0; s < kMaxK; ++s) lds_row<R>(win + s * TJ, lane, c[s]);
+                const float ws[kMaxK] = {wv[t].x, wv[t].y, wv[t].z, wv[t].w};
+#pragma unroll
+                for (int s = 0; s < kMaxK; ++s)
+#pragma unroll
+                    for (int r = 0; r < R; ++r) acc[t][r] = fmaf(ws[s], c[s][r], acc[t][r]);
+#pragma unroll
+                for (int r = 0; r < R; ++r) acc[t][r] = fmaf(bv[t].x, wb[r], acc[t][r]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            slab_store<NT, NQ, MASK>(q, map, nxt, tid);
+            __syncthreads();
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        if (b0 + t < B) {
+#pragma unroll
+            for (int h = 0; h < R / 4; ++h) {
+                const int j = j0 + h * 256 + lane * 4;
+                if (j < g.n_out) {
+                    float4 o = make_float4(acc[t][4 * h], acc[t][4 * h + 1], acc[t][4 * h + 2], acc[t][4 * h + 3]);
+                    *reinterpret_cast<float4 *>(y + (b0 + t) * g.n_out + j) = o;
+                }
+            }
+        }
+    }
+}
+
 // ---- launch --------------------------------------------------------------------------
 
 namespace {
@@ -246,9 +348,28 @@ size_t lds_bytes(int rows, int R, int NW) { return 2ull * (size_t)quads_needed(r
 int forward_lds_plan(const SplineGeom &g)
 {
     if (g.rows < kMaxK || g.n_out % 4 != 0 || g.slab_rows != g.rows + 1) return 0;
-    if (g.n_out > 256 && quads_needed(g.rows, 8, 16) && lds_bytes(g.rows, 8, 16) <= kLdsBudget) return 8;
+    // eight outputs per lane: two slabs and the waves' pair areas (32 KB) must fit, the slab in at most 4 quads per thread
+    if (g.n_out > 256 && quads_needed(g.rows, 8, 16) && quads_needed(g.rows, 8, 16) <= 4 &&
+        lds_bytes(g.rows, 8, 16) + 16 * 64 * 8 * sizeof(float) <= kLdsBudget)
+        return 8;
     if (g.n_out >= 128 && quads_needed(g.rows, 4, 8) && lds_bytes(g.rows, 4, 8) <= kLdsBudget) return 4;
     return 0;
+}
+
+template <int R, int T, int NW, int NQ>
+static hipError_t forward_pairs_launch(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
+                                       hipStream_t st)
+{
+    const size_t lds = 2ull * NQ * 64 * NW * 16 + (size_t)NW * 64 * 8 * sizeof(float);
+    const bool mask = (g.n_out % (64 * R)) != 0 || (int64_t)g.slab_rows * (64 * R / 4) != (int64_t)NQ * 64 * NW;
+    auto kern = mask ? forward_pairs_kernel<R, T, NW, NQ, true> : forward_pairs_kernel<R, T, NW, NQ, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((B + NW * T - 1) / (NW * T)), (unsigned)((g.n_out + 64 * R - 1) / (64 * R)));
+    prof::Timed tm("forward_pairs", st);
+    kern<<<grid, 64 * NW, lds, st>>>(g, x, cf, y, B);
+    return hipGetLastError();
 }
 
 template <int R, int T, int NW, int NQ>
@@ -284,11 +405,23 @@ static hipError_t forward_lds_by_quads(const SplineGeom &g, const float *x, cons
     }
 }
 
+template <int R, int T, int NW>
+static hipError_t forward_pairs_by_quads(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
+                                         hipStream_t st)
+{
+    switch (quads_needed(g.rows, R, NW)) {
+    case 2: return forward_pairs_launch<R, T, NW, 2>(g, x, cf, y, B, st);
+    case 3: return forward_pairs_launch<R, T, NW, 3>(g, x, cf, y, B, st);
+    case 4: return forward_pairs_launch<R, T, NW, 4>(g, x, cf, y, B, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
                               hipStream_t st)
 {
     switch (forward_lds_plan(g)) {
-    case 8: return forward_lds_by_quads<8, 4, 16>(g, x, cf, y, B, st);
+    case 8: return forward_pairs_by_quads<8, 4, 16>(g, x, cf, y, B, st);
     case 4: return forward_lds_by_quads<4, 16, 8>(g, x, cf, y, B, st);
     default: return hipErrorInvalidValue;
     }

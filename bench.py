@@ -5,12 +5,19 @@ One step = forward + backward (every gradient) of every layer of the workload on
 synthetic samples resident in HBM.  The default workload is the 512->512, G=20, k=3 layer on a batch
 of 16384 (the configuration the headline metric is quoted on).  Prints one JSON line with the
 whole-job throughput in edge-evaluations/s, the roofline position of the dominant kernel (its
-duration is measured with HIP events on the launch stream, inside the timed region) and the CPU
-oracle timed on the host cores on a bounded sample of the same workload.
+duration is measured with HIP events on the launch stream) and the CPU oracle timed on the host
+cores on a bounded sample of the same workload.
+
+The headline (ms_per_step, value) is timed with the library's launch observer OFF: exactly --steps
+steps between two device synchronisations, nothing else on the stream.  The per-kernel split behind
+`roofline` comes from a second pass over the same steps with the event-timing observer of the
+benchmark library installed (two events per launch, which costs a few microseconds per launch and is
+why it is not part of the headline).
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,13 +33,28 @@ def flops_per_edge(k):
     return 2 * (k + 1) + 2
 
 
-# HBM-side bytes per launch on the config-3 workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by a 1 GiB copy (profiles/kan_c3_fwd_bwd_hbm_traffic.md): read + written.  Only valid for
-# that workload and these kernels.
-MEASURED_TRAFFIC_BYTES_C3 = {
-    "forward_lds": 234.9e6 + 33.6e6,
-    "backward_walk": 1105.7e6 + 826.6e6,
-}
+# HBM-side bytes per launch of the dominant kernels are not measured here (that takes rocprofv3 counter
+# runs): they are read from the tracked summary of those runs, which carries one machine-readable line
+#   <!-- bench-traffic {"workload": "c3", "source_commit": "...", "kernels": {family: {"read": bytes, "written": bytes}}} -->
+# `traffic` is null when the file, the workload or the kernel family does not match what ran.
+TRAFFIC_FILE = os.path.join("profiles", "kan_c3_fwd_bwd_hbm_traffic.md")
+
+
+def measured_traffic(workload, family):
+    try:
+        text = open(os.path.join(ROOT, TRAFFIC_FILE)).read()
+    except OSError:
+        return None, None
+    m = re.search(r"<!-- bench-traffic (\{.*\}) -->", text)
+    if not m:
+        return None, None
+    rec = json.loads(m.group(1))
+    k = rec.get("kernels", {}).get(family)
+    if rec.get("workload") != workload or not k:
+        return None, None
+    return k["read"] + k["written"], {"file": TRAFFIC_FILE, "source_commit": rec.get("source_commit"),
+                                      "read": k["read"], "written": k["written"]}
+
 
 # kernel family -> which third of the fwd+bwd work it carries ("backward" = dL/dx and the parameter
 # gradients in one kernel: two thirds)
@@ -74,22 +96,94 @@ class KanCase:
         self.forward()
         self.backward()
 
-    def cpu_baseline(self, oracle):
+    def cpu_baseline(self, oracle, reps=3, rows=None):
         w, s, p = self.w, self.s, self.w.params[0]
         inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
-        reps = 3
+        n = w.B if rows is None else min(rows, w.B)
+        x, gy = w.x[:n], w.gy[:n]
         c0 = time.perf_counter()
         for _ in range(reps):
-            oracle.kan_forward(w.x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h, s.base_act)
-            oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h, s.base_act)
+            oracle.kan_forward(x, p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h, s.base_act)
+            oracle.kan_backward(x, p["coef"], p["w_s"], p["w_b"], gy, s.G, s.k, s.grid_lo, inv_h, s.base_act)
         c1 = time.perf_counter()
-        return reps * self.edges / (c1 - c0), "the whole batch (%d rows), forward + backward, %d repetitions, %.1f s" % (
+        return reps * n * s.n_in * s.n_out / (c1 - c0), "rows 0..%d of the batch of %d, forward + backward, %d repetitions, %.1f s" % (
+            n - 1, w.B, reps, c1 - c0)
+
+
+    def cpu_baseline_single(self, oracle):
+        # about a quarter of a minute on one core: 1.2e9 edge evaluations
+        rows = max(1, min(self.w.B, int(1.2e9 / (self.s.n_in * self.s.n_out))))
+        return self.cpu_baseline(oracle, reps=1, rows=rows)
+
+
+class KanStackCase:
+    """A stack of bounded-grid layers trained against a target (the small [2,5,1] network): forward through
+    every layer, dL/dy of the mean-squared error (one elementwise torch op, host-side glue between the layer
+    calls), backward through every layer."""
+
+    def __init__(self, w, torch, binding):
+        self.binding, self.w, self.torch = binding, w, torch
+        dev = lambda a: torch.from_numpy(a).cuda()
+        self.P = [{n: dev(a) for n, a in p.items()} for p in w.params]
+        self.target = dev(w.target)
+        B = w.B
+        self.acts = [dev(w.x)] + [torch.empty((B, s.n_out), device="cuda") for s in w.layers]
+        self.gacts = [torch.empty((B, s.n_in), device="cuda") for s in w.layers] + [torch.empty((B, w.layers[-1].n_out), device="cuda")]
+        self.outs = [{"gx": self.gacts[l], "gcoef": torch.empty_like(p["coef"]), "gw_s": torch.empty_like(p["w_s"]),
+                      "gw_b": torch.empty_like(p["w_b"])} for l, p in enumerate(self.P)]
+        self.ws_f = [torch.empty(binding.kan_workspace_bytes(s, B, binding.PASS_FORWARD), dtype=torch.uint8, device="cuda")
+                     for s in w.layers]
+        self.ws_b = [torch.empty(binding.kan_workspace_bytes(s, B, binding.PASS_BACKWARD), dtype=torch.uint8, device="cuda")
+                     for s in w.layers]
+        self.edges = sum(B * s.n_in * s.n_out for s in w.layers)
+        self.k = w.layers[0].k
+        self.config = {"workload": w.name, "B": B, "widths": [w.layers[0].n_in] + [s.n_out for s in w.layers],
+                       "G": w.layers[0].G, "k": self.k, "pass": "forward+mse+backward"}
+
+    def forward(self):
+        for l, (s, p) in enumerate(zip(self.w.layers, self.P)):
+            self.binding.kan_forward(s, self.acts[l], p["coef"], p["w_s"], p["w_b"], y=self.acts[l + 1], ws=self.ws_f[l])
+
+    def backward(self):
+        self.torch.sub(self.acts[-1], self.target, out=self.gacts[-1]).mul_(2.0 / self.w.B)
+        for l in reversed(range(len(self.w.layers))):
+            s, p = self.w.layers[l], self.P[l]
+            self.binding.kan_backward(s, self.acts[l], p["coef"], p["w_s"], p["w_b"], self.gacts[l + 1],
+                                      out=self.outs[l], ws=self.ws_b[l])
+
+    def step(self):
+        self.forward()
+        self.backward()
+
+    def cpu_baseline(self, oracle, reps=2000):
+        w = self.w
+        import numpy as np
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            acts = [w.x]
+            for s, p in zip(w.layers, w.params):
+                inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+                acts.append(np.float32(oracle.kan_forward(acts[-1], p["coef"], p["w_s"], p["w_b"], s.G, s.k, s.grid_lo, inv_h,
+                                                          s.base_act)))
+            g = np.float32(2.0 / w.B * (acts[-1].astype(np.float64) - w.target))
+            for l in reversed(range(len(w.layers))):
+                s, p = w.layers[l], w.params[l]
+                inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
+                g = np.float32(oracle.kan_backward(acts[l], p["coef"], p["w_s"], p["w_b"], g, s.G, s.k, s.grid_lo, inv_h,
+                                                   s.base_act)["gx"])
+        c1 = time.perf_counter()
+        return reps * self.edges / (c1 - c0), "the whole batch (%d rows), both layers forward + backward, %d repetitions, %.1f s" % (
             w.B, reps, c1 - c0)
 
 
+    def cpu_baseline_single(self, oracle):
+        return self.cpu_baseline(oracle, reps=500)
+
+
 class UkanCase:
-    """The UKAN stack: ukan_cg_forward + ukan_cg_backward of every layer.  The incoming gradient of
-    each layer is a fixed synthetic tensor (the true chained gradient, rescaled to unit RMS, taken
+    """The UKAN stack: ukan_cg_forward_saved + ukan_cg_backward_saved of every layer (the backward pass
+    reuses the group span, the CG activations and the coefficient table its forward pass kept).  The
+    incoming gradient of each layer is a fixed synthetic tensor (the true chained gradient, rescaled to unit RMS, taken
     once before the timed region), so every step does identical work."""
 
     def __init__(self, w, torch, binding):
@@ -108,6 +202,8 @@ class UkanCase:
             gx = binding.ukan_cg_backward(w.layers[l], self.acts[l], self.P[l], g, mg, want=["gx"])["gx"]
             g = (gx / gx.pow(2).mean().sqrt()).contiguous()
         self.outs, self.ws_f, self.ws_b = [], [], []
+        self.saved = [torch.empty(binding.ukan_saved_bytes(s, mg), dtype=torch.uint8, device="cuda") for s in w.layers]
+        self.span = [0] * L
         for l, s in enumerate(w.layers):
             K = s.k + 1
             self.outs.append({
@@ -129,21 +225,26 @@ class UkanCase:
     def forward(self):
         b, w, mg = self.binding, self.w, UKAN_MAX_GROUPS
         for l, s in enumerate(w.layers):
-            b.ukan_cg_forward(s, self.acts[l], self.P[l], mg, y=self.acts[l + 1], ws=self.ws_f[l])
+            _, _, self.span[l] = b.ukan_cg_forward_saved(s, self.acts[l], self.P[l], mg, saved=self.saved[l],
+                                                         y=self.acts[l + 1], ws=self.ws_f[l])
 
     def backward(self):
         b, w, mg = self.binding, self.w, UKAN_MAX_GROUPS
         for l in reversed(range(len(w.layers))):
-            b.ukan_cg_backward(w.layers[l], self.acts[l], self.P[l], self.gys[l], mg, out=self.outs[l], ws=self.ws_b[l])
+            b.ukan_cg_backward_saved(w.layers[l], self.acts[l], self.P[l], self.gys[l], mg, self.saved[l], self.span[l],
+                                     out=self.outs[l], ws=self.ws_b[l])
 
     def step(self):
         self.forward()
         self.backward()
 
-    def cpu_baseline(self, oracle):
+    def cpu_baseline_single(self, oracle):
+        return self.cpu_baseline(oracle, rows=512)
+
+    def cpu_baseline(self, oracle, rows=4096):
         # first layer only, on a slice of the batch, scaled by its share of the edge evaluations
         w, s, p = self.w, self.w.layers[0], self.w.params[0]
-        n = min(w.B, 4096)
+        n = min(w.B, rows)
         x = w.x[:n]
         inv_h = oracle.inv_h_of_spacing(s.h)
         gy = self.gys[0][:n].cpu().numpy()
@@ -160,11 +261,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "p"],
-                    help="c2..c5: the benchmark configurations; p: the paper's 32->32, N=2^17 shape (see --grid)")
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "p"],
+                    help="c1..c5: the benchmark configurations; p: the paper's 32->32, N=2^17 shape (see --grid)")
     ap.add_argument("--grid", type=int, default=64, help="grid size G of workload p")
-    ap.add_argument("--degree", type=int, default=3, help="spline degree k of workload p (1..3)")
+    ap.add_argument("--degree", type=int, default=3, help="spline degree k of workload p (1..5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=10,
+                    help="steps of the separate pass that times every kernel with events (0: skip it)")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="also time the dense basis x coefficient GEMM formulation of the forward pass")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -185,6 +288,8 @@ def main():
 
     if args.workload == "c5":
         case = UkanCase(workloads.config5(), torch, binding)
+    elif args.workload == "c1":
+        case = KanStackCase(workloads.config1(), torch, binding)
     else:
         w = {"c2": workloads.config2, "c3": workloads.config3, "c4": workloads.config4,
              "p": lambda: workloads.paper_shape(args.grid, k=args.degree)}[args.workload]()
@@ -198,28 +303,41 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # headline: the launch observer is off, nothing but the steps runs between the two synchronisations
+    binding.kan_set_launch_observer(None, None)
     for _ in range(args.warmup):
         case.step()
     torch.cuda.synchronize()
-    binding.kan_profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         case.step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    binding.kan_profile_enable(False)
-    kt = binding.kan_profile_read()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     edges = case.edges
     value = edges / (ms_per_step * 1e-3)
 
+    # per-kernel split: a separate pass with an event pair around every launch
+    psteps = max(args.profile_steps, 0)
+    kt = {}
+    ms_per_step_profiled = None
+    if psteps:
+        binding.kan_profile_enable(True)
+        p0 = time.perf_counter()
+        for _ in range(psteps):
+            case.step()
+        torch.cuda.synchronize()
+        ms_per_step_profiled = (time.perf_counter() - p0) * 1e3 / psteps
+        binding.kan_profile_enable(False)
+        kt = binding.kan_profile_read()
+
     # dominant kernel = largest total time per step; its roofline position uses the edge evaluations
     # it processes per step and the multiply-adds the method needs for its share of the pass
-    per_step = {n: tot / args.steps for n, (tot, cnt) in kt.items()}
-    launches = {n: cnt / args.steps for n, (tot, cnt) in kt.items()}
-    dom = max(per_step, key=per_step.get)
-    dom_ms = per_step[dom]
-    if dom in KERNEL_ROLE:
+    per_step = {n: tot / psteps for n, (tot, cnt) in kt.items()}
+    launches = {n: cnt / psteps for n, (tot, cnt) in kt.items()}
+    dom = max(per_step, key=per_step.get) if per_step else None
+    dom_ms = per_step[dom] if dom else None
+    if dom in KERNEL_ROLE and isinstance(case, KanCase):
         flops = flops_per_edge(case.k) * ROLE_SHARE[KERNEL_ROLE[dom]] * edges
         achieved = flops / (dom_ms * 1e-3) / 1e12
     else:
@@ -227,10 +345,13 @@ def main():
     peak = roofline.MI355X_FP32_VECTOR_FLOPS / 1e12
     # the walk kernels run the window-row multiply-adds on the matrix cores (fp32 MFMA peak = fp32 vector peak)
     bound = "mfma" if dom in ("backward_walk", "dparam_walk") else "alu"
+    traffic, traffic_source = measured_traffic(args.workload, dom)
     rl = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
           "frac": (achieved / peak) if achieved else None,
-          "traffic": MEASURED_TRAFFIC_BYTES_C3.get(dom) if args.workload == "c3" else None,
-          "kernel_ms": dom_ms / max(launches[dom], 1), "kernel_launches_per_step": launches[dom],
+          "traffic": traffic, "traffic_source": traffic_source,
+          "kernel_ms": (dom_ms / max(launches[dom], 1)) if dom else None,
+          "kernel_launches_per_step": launches[dom] if dom else None,
+          "profiled_steps": psteps, "ms_per_step_profiled": ms_per_step_profiled,
           "peak_unpacked": roofline.MI355X_FP32_VECTOR_FLOPS_UNPACKED / 1e12,
           "frac_unpacked": (achieved / (roofline.MI355X_FP32_VECTOR_FLOPS_UNPACKED / 1e12)) if achieved else None,
           "whole_path_frac": roofline.algorithmic_flops_per_edge(case.k + 1) * value / roofline.MI355X_FP32_VECTOR_FLOPS,
@@ -253,7 +374,7 @@ def main():
     dense = None
     if args.dense_baseline and isinstance(case, KanCase):
         s = case.s
-        ws_d = torch.empty(binding.load().kan_dense_baseline_workspace_bytes(binding.kan_desc(s), case.w.B),
+        ws_d = torch.empty(binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_FORWARD),
                            dtype=torch.uint8, device="cuda")
         for _ in range(2):
             binding.kan_dense_baseline_forward(s, case.x, case.coef, case.w_s, case.w_b, y=case.y, ws=ws_d)
@@ -265,7 +386,7 @@ def main():
         dense_ms = (time.perf_counter() - d0) * 1e3 / 5
         fwd_ms = sum(v for n, v in per_step.items() if KERNEL_ROLE.get(n) == "forward") + per_step.get("fold_scale", 0.0) / 2
         del ws_d
-        ws_d = torch.empty(binding.load().kan_dense_baseline_backward_workspace_bytes(binding.kan_desc(s), case.w.B),
+        ws_d = torch.empty(binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_BACKWARD),
                            dtype=torch.uint8, device="cuda")
         for _ in range(2):
             binding.kan_dense_baseline_backward(s, case.x, case.coef, case.w_s, case.w_b, case.gy, out=case.out, ws=ws_d)
@@ -277,14 +398,24 @@ def main():
         dense_bwd_ms = (time.perf_counter() - d0) * 1e3 / 5
         dense = {"forward_ms_dense_gemm": dense_ms, "forward_ms_local": fwd_ms,
                  "backward_ms_dense_gemm": dense_bwd_ms, "backward_ms_local": ms_per_step - fwd_ms,
+                 "workspace_bytes_dense": [binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_FORWARD),
+                                           binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_BACKWARD)],
+                 "workspace_bytes_local": [binding.kan_workspace_bytes(s, case.w.B, binding.PASS_FORWARD),
+                                           binding.kan_workspace_bytes(s, case.w.B, binding.PASS_BACKWARD)],
                  "note": "dense = expand all G+k bases (and their x-derivatives) + rocBLAS sgemm"}
         del ws_d
 
+    # the oracle as it stands, on all the host threads it takes, then on one thread on a smaller sample
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         v, sample = case.cpu_baseline(oracle)
         cpu = {"value": v, "unit": "edge-evals/s", "cores": oracle.num_threads(), "kind": "oracle", "sample": sample}
+        all_threads = oracle.num_threads()
+        oracle.set_num_threads(1)
+        v1, sample1 = case.cpu_baseline_single(oracle)
+        cpu["single_thread"] = {"value": v1, "unit": "edge-evals/s", "cores": oracle.num_threads(), "sample": sample1}
+        oracle.set_num_threads(all_threads)
 
     line = {"metric": "KAN layer fwd+bwd edge-evals/sec (B*n_in*n_out)", "value": value, "unit": "edge-evals/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -9,9 +9,11 @@
  * Conventions that hold for every entry point
  *   - Every pointer argument is DEVICE memory owned by the caller unless it is
  *     a descriptor / parameter struct, which is HOST memory read during the
- *     call.  The library allocates nothing and keeps no state between calls;
- *     scratch space comes in through (ws, ws_bytes) and must be at least what
- *     the matching *_workspace_bytes call returns (256-byte aligned).
+ *     call.  The library allocates nothing, links nothing but the HIP runtime
+ *     and keeps no state between calls (the two exceptions, the launch observer
+ *     and the built-in array of kan_forward_static, say so where they are
+ *     declared); scratch space comes in through (ws, ws_bytes) and must be at
+ *     least what the matching *_workspace_bytes call returns (256-byte aligned).
  *   - `stream` is a hipStream_t passed as void*.  All work is enqueued on it.
  *     kan_* calls never synchronise; the ukan_* calls synchronise the stream
  *     once to read back the group span (4 bytes), see below.
@@ -136,38 +138,16 @@ int kan_forward_static(const kan_layer_desc *desc, int64_t B, const float *x, co
 int kan_interval_index(const kan_layer_desc *desc, int64_t n, const float *x, int32_t *idx,
                        void *stream);
 
-/* ---- diagnostics ------------------------------------------------------------------------ */
+/* ---- launch observer ---------------------------------------------------------------------- */
 
-/* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
-   bracketed by a pair of HIP events on the launch stream (the only library state that outlives
-   a call; at most 8192 launches are recorded, later ones run untimed).  kan_profile_enable(1)
-   clears earlier records, kan_profile_enable(0) stops recording.  kan_profile_read waits for
-   the recorded events, fills up to `capacity` entries (one per kernel family, `name` is a
-   static string) and returns the number of families seen, or a negative kan_status.
-   Not thread-safe; meant for one benchmarking thread. */
-typedef struct kan_kernel_time {
-    const char *name;
-    double total_ms;
-    int64_t launches;
-} kan_kernel_time;
-int kan_profile_enable(int on);
-int kan_profile_read(kan_kernel_time *out, int capacity);
-
-/* Comparison baseline, not the product path: the forward pass written as one dense GEMM
-   y = Phi * C over all G + k basis functions per input (the O(G) formulation of table "Complexity",
-   row "Torch KAN"), with Phi materialised in the workspace and the contraction done by rocBLAS.
-   Unlike every other entry point it creates a rocBLAS handle on first use (which allocates) and
-   keeps it for the life of the process. */
-size_t kan_dense_baseline_workspace_bytes(const kan_layer_desc *desc, int64_t B);
-int kan_dense_baseline_forward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
-                               const float *w_s, const float *w_b, float *y, void *ws, size_t ws_bytes,
-                               void *stream);
-/* The dense backward pass of the same baseline: gPhi = gy * C^T and gC = Phi^T * gy by rocBLAS, dL/dx as the row-wise
-   product of gPhi with dPhi/dx.  Same outputs and conventions as kan_backward. */
-size_t kan_dense_baseline_backward_workspace_bytes(const kan_layer_desc *desc, int64_t B);
-int kan_dense_baseline_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
-                                const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
-                                float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream);
+/* Two optional host callbacks, process-wide: `before` is called on the calling thread right before
+   each kernel launch of the library is enqueued and `after` right after it, with a static string
+   naming the kernel family and the launch stream.  Either may be NULL; (NULL, NULL), the initial
+   state, switches the observer off.  The two pointers are the only state the library keeps besides
+   the array of kan_forward_static.  Meant for measurement (the benchmark library of kan_bench.h
+   records a HIP event in each); do not change the observer while another thread is inside a call. */
+typedef void (*kan_launch_hook)(const char *family, void *stream);
+int kan_set_launch_observer(kan_launch_hook before, kan_launch_hook after);
 
 /* ---- UKAN ------------------------------------------------------------------------------ */
 
@@ -187,12 +167,33 @@ int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, cons
 
 /* UKAN backward given gy: gx (through the local coordinate only; the group index is piecewise
    constant), and the gradients of every CG parameter, of scale and of w_b.  Recomputes steps 1-2
-   of the forward pass; same synchronisation and error behaviour. */
+   of the forward pass; same synchronisation and error behaviour.  A training step that has run the
+   forward pass on the same x and parameters should use the *_saved pair below instead. */
 int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
                      const float *gy, float *gx, const ukan_grads *g, int32_t max_groups, void *ws,
                      size_t ws_bytes, void *stream);
 
-/* UKAN -> KAN export (appendix "Converting UKAN to KAN"): the coefficients of the bounded-grid layer that
+/* Forward -> backward hand-off for training.  ukan_cg_forward_saved is ukan_cg_forward that also
+   keeps what steps 1-2 produced (first group and cell offset of every input, the CG's input rows,
+   hidden pre-activations and activations, the coefficient table with and without the scale) in
+   `saved`, caller-owned device memory of at least ukan_saved_bytes(desc, max_groups) bytes,
+   256-byte aligned, and writes the widest group span to *span (HOST memory; 0 on failure).
+   ukan_cg_backward_saved takes that buffer and span and runs only the steps after the table:
+   no range scan, no CG forward, no synchronisation.  x, p's contents and max_groups must be the
+   ones of the forward call, and `saved` must not have been written since; the library cannot
+   check this.  Results are bit-identical to ukan_cg_backward.  ws as for the unsaved calls
+   (ukan_workspace_bytes with the matching pass).  Errors as above; a span outside 2..max_groups
+   gives KAN_ERR_RANGE, a short or misaligned `saved` KAN_ERR_WORKSPACE. */
+size_t ukan_saved_bytes(const ukan_layer_desc *desc, int32_t max_groups);
+int ukan_cg_forward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                          float *y, int32_t max_groups, void *saved, size_t saved_bytes, int32_t *span,
+                          void *ws, size_t ws_bytes, void *stream);
+int ukan_cg_backward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                           const float *gy, float *gx, const ukan_grads *g, int32_t max_groups,
+                           const void *saved, size_t saved_bytes, int32_t span, void *ws, size_t ws_bytes,
+                           void *stream);
+
+/* UKAN -> KAN export (appendix "UKAN mapping to KAN in Inference"): the coefficients of the bounded-grid layer that
    equals this UKAN layer on the cells cell_lo .. cell_hi, i.e. on [cell_lo*h, (cell_hi+1)*h):
      coef[i][m][j] = scale[i][j] * CG(i, g)[q*n_out + j],   g*K + q = cell_lo - K + m,   m = 0 .. G + k - 1,
    G = cell_hi - cell_lo + 1.  Use it with kan_layer_desc{n_in, n_out, G, k, cell_lo*h, (cell_hi+1)*h, base_act},

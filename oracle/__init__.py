@@ -68,6 +68,11 @@ def num_threads():
     return int(_load().okan_num_threads())
 
 
+def set_num_threads(n):
+    """Threads the oracle's loops run on from now on (timing aid; results do not depend on it)."""
+    _load().okan_set_num_threads(int(n))
+
+
 def inv_h_of(grid_lo, grid_hi, G):
     """The fp32 reciprocal cell width both sides use: (float)G / (hi - lo)."""
     return np.float32(G) / (np.float32(grid_hi) - np.float32(grid_lo))

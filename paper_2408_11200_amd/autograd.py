@@ -1,7 +1,8 @@
 """torch.autograd glue around the C-ABI entry points.
 
-Nothing is computed here: `forward` calls kan_forward / ukan_cg_forward, `backward` calls
-kan_backward / ukan_cg_backward with exactly the gradients autograd asks for.  Lets a stack of
+Nothing is computed here: `forward` calls kan_forward / ukan_cg_forward_saved, `backward` calls
+kan_backward / ukan_cg_backward_saved with exactly the gradients autograd asks for (the UKAN
+backward pass reuses the coefficient table and the CG activations its forward pass kept).  Lets a stack of
 layers be trained with a stock PyTorch optimizer (closed-form regression targets of the paper's
 experiments section need nothing else).
 """
@@ -35,22 +36,24 @@ class _UkanLayer(torch.autograd.Function):
     @staticmethod
     def forward(ctx, spec, max_groups, x, E, W1, b1, W2, b2, scale, w_b):
         ctx.spec, ctx.max_groups = spec, max_groups
-        ctx.save_for_backward(x, E, W1, b1, W2, b2, scale, w_b)
         p = dict(zip(_UKAN_NAMES, (E, W1, b1, W2, b2, scale)))
         if w_b is not None:
             p["w_b"] = w_b
-        return binding.ukan_cg_forward(spec, x.contiguous(), p, max_groups)
+        y, saved, ctx.span = binding.ukan_cg_forward_saved(spec, x.contiguous(), p, max_groups)
+        ctx.save_for_backward(x, E, W1, b1, W2, b2, scale, w_b, saved)
+        return y
 
     @staticmethod
     def backward(ctx, gy):
-        x, E, W1, b1, W2, b2, scale, w_b = ctx.saved_tensors
+        x, E, W1, b1, W2, b2, scale, w_b, saved = ctx.saved_tensors
         p = dict(zip(_UKAN_NAMES, (E, W1, b1, W2, b2, scale)))
         if w_b is not None:
             p["w_b"] = w_b
         names = ("gx", "gE", "gW1", "gb1", "gW2", "gb2", "gscale", "gw_b")
         need = ctx.needs_input_grad[2:10]
         want = [n for n, k in zip(names, need) if k and not (n == "gw_b" and w_b is None)]
-        g = binding.ukan_cg_backward(ctx.spec, x.contiguous(), p, gy.contiguous(), ctx.max_groups, want=want) if want else {}
+        g = binding.ukan_cg_backward_saved(ctx.spec, x.contiguous(), p, gy.contiguous(), ctx.max_groups, saved,
+                                           ctx.span, want=want) if want else {}
         return (None, None) + tuple(g.get(n) for n in names)
 
 

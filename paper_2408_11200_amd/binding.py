@@ -1,4 +1,5 @@
-"""ctypes front end of libkan_hip.so: same entry-point names as include/kan.h.
+"""ctypes front end of libkan_hip.so (include/kan.h) and of the benchmark companion libkan_bench.so
+(include/kan_bench.h): same entry-point names as the headers.
 
 Argument marshalling only.  PyTorch is used to hold device memory and to name
 the stream; every step of the layer runs inside the HIP library.  If the
@@ -11,6 +12,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkan_hip.so")
+BENCH_LIB_PATH = os.path.join(_HERE, "libkan_bench.so")
 
 KAN_OK = 0
 KAN_ERR_INVALID_ARG = -1
@@ -21,12 +23,15 @@ KAN_ERR_HIP = -5
 PASS_FORWARD, PASS_BACKWARD = 0, 1
 
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
-           "kan_static_scratch_bytes", "kan_forward_static",
-           "kan_profile_enable", "kan_profile_read", "kan_dense_baseline_workspace_bytes",
-           "kan_dense_baseline_forward", "kan_dense_baseline_backward_workspace_bytes",
-           "kan_dense_baseline_backward",
-           "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_materialize_workspace_bytes",
+           "kan_static_scratch_bytes", "kan_forward_static", "kan_set_launch_observer",
+           "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_saved_bytes",
+           "ukan_cg_forward_saved", "ukan_cg_backward_saved", "ukan_materialize_workspace_bytes",
            "ukan_materialize", "ukan_group_index"]
+
+
+BENCH_EXPORTS = ["kan_profile_before", "kan_profile_after", "kan_profile_enable", "kan_profile_read",
+                 "kan_dense_baseline_workspace_bytes", "kan_dense_baseline_forward",
+                 "kan_dense_baseline_backward_workspace_bytes", "kan_dense_baseline_backward"]
 
 
 class KanLayerDesc(ctypes.Structure):
@@ -85,6 +90,46 @@ def load():
     lib.kan_backward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kan_interval_index.restype = ctypes.c_int
     lib.kan_interval_index.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp]
+    lib.kan_set_launch_observer.restype = ctypes.c_int
+    lib.kan_set_launch_observer.argtypes = [vp, vp]
+    lib.ukan_workspace_bytes.restype = sz
+    lib.ukan_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i32, ctypes.c_int]
+    lib.ukan_cg_forward.restype = ctypes.c_int
+    lib.ukan_cg_forward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, i32,
+                                    vp, sz, vp]
+    lib.ukan_cg_backward.restype = ctypes.c_int
+    lib.ukan_cg_backward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, vp,
+                                     ctypes.POINTER(UkanGrads), i32, vp, sz, vp]
+    lib.ukan_saved_bytes.restype = sz
+    lib.ukan_saved_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i32]
+    lib.ukan_cg_forward_saved.restype = ctypes.c_int
+    lib.ukan_cg_forward_saved.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, i32,
+                                          vp, sz, ctypes.POINTER(i32), vp, sz, vp]
+    lib.ukan_cg_backward_saved.restype = ctypes.c_int
+    lib.ukan_cg_backward_saved.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, vp,
+                                           ctypes.POINTER(UkanGrads), i32, vp, sz, i32, vp, sz, vp]
+    lib.ukan_materialize_workspace_bytes.restype = ctypes.c_size_t
+    lib.ukan_materialize_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i64]
+    lib.ukan_materialize.restype = ctypes.c_int
+    lib.ukan_materialize.argtypes = [ctypes.POINTER(UkanLayerDesc), ctypes.POINTER(UkanParams), i64, i64, vp, vp, sz, vp]
+    lib.ukan_group_index.restype = ctypes.c_int
+    lib.ukan_group_index.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+_bench = None
+
+
+def load_bench():
+    """Load the benchmark companion library (event timing, dense baseline); raise if it is missing."""
+    global _bench
+    if _bench is not None:
+        return _bench
+    if not os.path.exists(BENCH_LIB_PATH):
+        raise RuntimeError("%s is missing: build it with `python -m paper_2408_11200_amd.build`" % BENCH_LIB_PATH)
+    lib = ctypes.CDLL(BENCH_LIB_PATH)
+    vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
     lib.kan_profile_enable.restype = ctypes.c_int
     lib.kan_profile_enable.argtypes = [ctypes.c_int]
     lib.kan_profile_read.restype = ctypes.c_int
@@ -98,21 +143,7 @@ def load():
                                                 vp, sz, vp]
     lib.kan_dense_baseline_forward.restype = ctypes.c_int
     lib.kan_dense_baseline_forward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, sz, vp]
-    lib.ukan_workspace_bytes.restype = sz
-    lib.ukan_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i32, ctypes.c_int]
-    lib.ukan_cg_forward.restype = ctypes.c_int
-    lib.ukan_cg_forward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, i32,
-                                    vp, sz, vp]
-    lib.ukan_cg_backward.restype = ctypes.c_int
-    lib.ukan_cg_backward.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, vp,
-                                     ctypes.POINTER(UkanGrads), i32, vp, sz, vp]
-    lib.ukan_materialize_workspace_bytes.restype = ctypes.c_size_t
-    lib.ukan_materialize_workspace_bytes.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, i64]
-    lib.ukan_materialize.restype = ctypes.c_int
-    lib.ukan_materialize.argtypes = [ctypes.POINTER(UkanLayerDesc), ctypes.POINTER(UkanParams), i64, i64, vp, vp, sz, vp]
-    lib.ukan_group_index.restype = ctypes.c_int
-    lib.ukan_group_index.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, vp, vp, vp, vp]
-    _lib = lib
+    _bench = lib
     return lib
 
 
@@ -217,9 +248,16 @@ def kan_interval_index(spec, x, stream=None):
     return idx
 
 
+def kan_dense_baseline_workspace_bytes(spec, B, which=PASS_FORWARD):
+    d = kan_desc(spec)
+    lib = load_bench()
+    return int(lib.kan_dense_baseline_workspace_bytes(ctypes.byref(d), B) if which == PASS_FORWARD
+               else lib.kan_dense_baseline_backward_workspace_bytes(ctypes.byref(d), B))
+
+
 def kan_dense_baseline_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=None):
     """Comparison baseline: the same forward pass as one dense GEMM over all basis functions."""
-    lib = load()
+    lib = load_bench()
     d = kan_desc(spec)
     B = x.shape[0]
     if y is None:
@@ -235,7 +273,7 @@ def kan_dense_baseline_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=
 
 def kan_dense_baseline_backward(spec, x, coef, w_s, w_b, gy, out=None, ws=None, stream=None):
     """Comparison baseline: the backward pass as two dense GEMMs over all basis functions."""
-    lib = load()
+    lib = load_bench()
     d = kan_desc(spec)
     B = x.shape[0]
     shapes = {"gx": (B, spec.n_in), "gcoef": (spec.n_in, spec.G + spec.k, spec.n_out),
@@ -254,14 +292,29 @@ def kan_dense_baseline_backward(spec, x, coef, w_s, w_b, gy, out=None, ws=None, 
     return out
 
 
+def kan_set_launch_observer(before, after):
+    """Install two C function pointers (or None) as the layer library's launch observer."""
+    as_vp = lambda f: None if f is None else ctypes.cast(f, ctypes.c_void_p)
+    rc = load().kan_set_launch_observer(as_vp(before), as_vp(after))
+    if rc != KAN_OK:
+        raise KanError(rc, "kan_set_launch_observer")
+
+
 def kan_profile_enable(on):
-    load().kan_profile_enable(1 if on else 0)
+    """Start (clearing earlier records) or stop per-kernel event timing: installs the benchmark library's
+    hooks as the layer library's launch observer, or removes them."""
+    bench = load_bench()
+    if on:
+        kan_set_launch_observer(bench.kan_profile_before, bench.kan_profile_after)
+    else:
+        kan_set_launch_observer(None, None)
+    bench.kan_profile_enable(1 if on else 0)
 
 
 def kan_profile_read():
     """{kernel family: (total_ms, launches)} of the launches recorded since kan_profile_enable(True)."""
     arr = (KanKernelTime * 64)()
-    n = load().kan_profile_read(arr, 64)
+    n = load_bench().kan_profile_read(arr, 64)
     if n < 0:
         raise KanError(n, "kan_profile_read")
     return {arr[q].name.decode(): (arr[q].total_ms, int(arr[q].launches)) for q in range(min(n, 64))}
@@ -297,7 +350,34 @@ def ukan_cg_forward(spec, x, p, max_groups, y=None, ws=None, stream=None):
     return y
 
 
-def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, stream=None):
+def ukan_saved_bytes(spec, max_groups):
+    d = ukan_desc(spec)
+    return int(load().ukan_saved_bytes(ctypes.byref(d), max_groups))
+
+
+def ukan_cg_forward_saved(spec, x, p, max_groups, saved=None, y=None, ws=None, stream=None):
+    """ukan_cg_forward that keeps its intermediates for ukan_cg_backward_saved: returns (y, saved, span)."""
+    lib = load()
+    d = ukan_desc(spec)
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+    if saved is None:
+        saved = _workspace(lib.ukan_saved_bytes(ctypes.byref(d), max_groups), x.device)
+    if ws is None:
+        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_FORWARD), x.device)
+    pp = _ukan_params(p)
+    span = ctypes.c_int32(0)
+    rc = lib.ukan_cg_forward_saved(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(y), max_groups, _ptr(saved),
+                                   saved.numel(), ctypes.byref(span), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "ukan_cg_forward_saved")
+    return y, saved, int(span.value)
+
+
+def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, stream=None, saved=None, span=None):
+    """All gradients of one UKAN layer.  With `saved` and `span` from ukan_cg_forward_saved the call is
+    ukan_cg_backward_saved (no recomputation of the coefficient table, no synchronisation)."""
     lib = load()
     d = ukan_desc(spec)
     B = x.shape[0]
@@ -315,11 +395,21 @@ def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, s
     pp = _ukan_params(p)
     gg = UkanGrads(*[(out[n].data_ptr() if n in out else None)
                      for n in ("gE", "gW1", "gb1", "gW2", "gb2", "gscale", "gw_b")])
-    rc = lib.ukan_cg_backward(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(gy), _f32(out.get("gx")),
-                              ctypes.byref(gg), max_groups, _ptr(ws), ws.numel(), _stream(stream))
+    if saved is not None:
+        rc = lib.ukan_cg_backward_saved(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(gy), _f32(out.get("gx")),
+                                        ctypes.byref(gg), max_groups, _ptr(saved), saved.numel(), int(span), _ptr(ws),
+                                        ws.numel(), _stream(stream))
+    else:
+        rc = lib.ukan_cg_backward(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(gy), _f32(out.get("gx")),
+                                  ctypes.byref(gg), max_groups, _ptr(ws), ws.numel(), _stream(stream))
     if rc != KAN_OK:
-        raise KanError(rc, "ukan_cg_backward")
+        raise KanError(rc, "ukan_cg_backward_saved" if saved is not None else "ukan_cg_backward")
     return out
+
+
+def ukan_cg_backward_saved(spec, x, p, gy, max_groups, saved, span, want=None, out=None, ws=None, stream=None):
+    return ukan_cg_backward(spec, x, p, gy, max_groups, want=want, out=out, ws=ws, stream=stream, saved=saved,
+                            span=span)
 
 
 def ukan_materialize(spec, p, cell_lo, cell_hi, coef=None, ws=None, stream=None):

@@ -5,7 +5,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-LIB_PATH = os.path.join(HERE, "libkan_hip.so")
+LIB_PATH = os.path.join(HERE, "libkan_hip.so")            # the layer library (HIP runtime only)
+BENCH_LIB_PATH = os.path.join(HERE, "libkan_bench.so")    # benchmark companion: event timing, rocBLAS dense baseline
 
 # packed fp32 instructions are switched off for every translation unit
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -20,10 +21,16 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build(verbose=False, jobs=None):
-    """Compile csrc/*.hip into libkan_hip.so next to this file.  Always recompiles.
+def bench_sources():
+    return sorted(glob.glob(os.path.join(HERE, "csrc_bench", "*.hip")))
 
-    Every source is compiled to an object file in its own hipcc process (a few at a time), then linked."""
+
+def build(verbose=False, jobs=None):
+    """Compile csrc/*.hip into libkan_hip.so and csrc_bench/*.hip into libkan_bench.so next to this file.
+    Always recompiles.
+
+    Every source is compiled to an object file in its own hipcc process (a few at a time), then each
+    library is linked from its own objects; only the benchmark library links rocBLAS."""
     import concurrent.futures
     import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -40,14 +47,19 @@ def build(verbose=False, jobs=None):
 
     with tempfile.TemporaryDirectory(prefix="kan_build_") as tmp:
         objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in sources()]
+        bench_objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in bench_sources()]
         with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
             results = list(pool.map(lambda so: run([hipcc] + flags + inc + ["-c", so[0], "-o", so[1]]),
-                                    zip(sources(), objs)))
+                                    zip(sources() + bench_sources(), objs + bench_objs)))
         failed = [out for rc, out in results if rc != 0]
         log += [out for rc, out in results if out]
-        if not failed:
-            rc, out = run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs +
-                          ["-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib", "-o", LIB_PATH])
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"]
+        for these, libs, path in ((objs, [], LIB_PATH),
+                                  (bench_objs, ["-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib"],
+                                   BENCH_LIB_PATH)):
+            if failed:
+                break
+            rc, out = run(link + these + libs + ["-o", path])
             if out:
                 log.append(out)
             if rc != 0:

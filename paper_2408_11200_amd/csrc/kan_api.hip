@@ -7,6 +7,17 @@
 
 using namespace kan;
 
+namespace kanprof {
+Hook g_before = nullptr, g_after = nullptr;
+}
+
+extern "C" int kan_set_launch_observer(kan_launch_hook before, kan_launch_hook after)
+{
+    kanprof::g_before = before;
+    kanprof::g_after = after;
+    return KAN_OK;
+}
+
 namespace {
 
 constexpr size_t kAlign = 256;

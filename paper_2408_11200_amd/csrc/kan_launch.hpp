@@ -6,17 +6,21 @@
 #include <stdint.h>
 #include "kan_device.hpp"
 
-// Optional per-launch timing (see kan_profile_enable in kan.h).  A Timed object brackets one
-// kernel launch with two events when profiling is on and does nothing otherwise.
+// Launch observer (kan_set_launch_observer in kan.h).  A Timed object calls the installed hooks on
+// the host right before and right after one kernel launch is enqueued, and does nothing when none
+// is installed.
 namespace kanprof {
-bool enabled();
-void begin(const char *family, hipStream_t st);
-void end(hipStream_t st);
+typedef void (*Hook)(const char *family, void *stream);
+extern Hook g_before, g_after;
 struct Timed {
+    const char *family;
     hipStream_t st;
-    bool on;
-    Timed(const char *family, hipStream_t s) : st(s), on(enabled()) { if (on) begin(family, st); }
-    ~Timed() { if (on) end(st); }
+    Hook after;
+    Timed(const char *f, hipStream_t s) : family(f), st(s), after(g_after)
+    {
+        if (Hook b = g_before) b(family, (void *)st);
+    }
+    ~Timed() { if (after) after(family, (void *)st); }
 };
 }  // namespace kanprof
 

@@ -101,24 +101,60 @@ Layout make_layout(const ukan_layer_desc *d, int64_t B, int64_t n_g, int n_chunk
     return L;
 }
 
+// What the forward pass hands to the backward pass (ukan_cg_forward_saved): everything steps 1-2
+// produce.  Offsets (bytes) into the caller's `saved` buffer for n_g generator rows per input.
+struct SavedLayout { size_t g_first, cell_base, hid, cf, z, pre, raw, total; };
+
+SavedLayout saved_layout(const ukan_layer_desc *d, int64_t n_g)
+{
+    const size_t K = (size_t)d->k + 1, n_in = (size_t)d->n_in, rows = n_in * (size_t)n_g;
+    const size_t table = align_up(rows * K * (size_t)d->n_out * sizeof(float));
+    const size_t dz = (size_t)d->d_feat + d->d_pe, dh = (size_t)d->d_hidden;
+    SavedLayout S;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t here = at; at += align_up(bytes); return here; };
+    S.g_first = take(n_in * 4); S.cell_base = take(n_in * 4);
+    S.hid = take(rows * dh * 4); S.cf = take(table);
+    S.z = take(rows * dz * 4); S.pre = take(rows * dh * 4); S.raw = take(table);
+    S.total = at;
+    return S;
+}
+
+// The products of steps 1-2, wherever they live (the workspace, or the caller's saved buffer).
 struct Prepared {
     SplineGeom g;
-    Layout L;
+    Layout L;          // scratch regions of the workspace
     int n_g;
     ChunkPlan cp;
+    int32_t *g_first, *cell_base;
+    float *hid, *cf, *z, *pre, *raw;     // z, pre, raw: null unless kept for the backward pass
 };
 
+void spline_geom(const ukan_layer_desc *d, int span, const int32_t *cell_base, SplineGeom *g)
+{
+    g->n_in = d->n_in; g->n_out = d->n_out;
+    g->rows = span * (d->k + 1); g->slab_rows = g->rows; g->k = d->k;
+    g->lo = 0.0f; g->inv_h = 1.0f / d->h;
+    g->cell_base = cell_base;
+    g->base_act = d->base_act;
+}
+
 // steps 1-2 of the pass: group range, read-back, CG forward into the table(s)
+// With `saved` the products go to the caller's buffer (laid out for the span found) and z, pre and
+// the unscaled table are kept whatever the pass.
 int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_params *p, int32_t max_groups,
-            char *ws, int pass, hipStream_t st, Prepared *out)
+            char *ws, int pass, hipStream_t st, Prepared *out, char *saved = nullptr)
 {
     const int K = d->k + 1;
     const float inv_h = 1.0f / d->h;
     out->cp = chunks_for(d, B, max_groups);
     Layout L0 = make_layout(d, B, max_groups, out->cp.n_chunks, record_bytes_for(d, B, max_groups), b_slices_for(d, B, max_groups), pass);     // meta offsets do not depend on n_g
     int32_t *cmin = (int32_t *)(ws + L0.cmin), *cmax = (int32_t *)(ws + L0.cmax);
-    int32_t *g_first = (int32_t *)(ws + L0.g_first), *n_groups = (int32_t *)(ws + L0.n_groups);
-    int32_t *cell_base = (int32_t *)(ws + L0.cell_base), *summary = (int32_t *)(ws + L0.summary);
+    int32_t *n_groups = (int32_t *)(ws + L0.n_groups), *summary = (int32_t *)(ws + L0.summary);
+    // the saved layout starts with g_first and cell_base at offsets that do not depend on the span
+    const SavedLayout S0 = saved_layout(d, max_groups);
+    int32_t *g_first = (int32_t *)(saved ? saved + S0.g_first : ws + L0.g_first);
+    int32_t *cell_base = (int32_t *)(saved ? saved + S0.cell_base : ws + L0.cell_base);
     if (launch_range(x, B, d->n_in, inv_h, K, cmin, cmax, g_first, n_groups, cell_base, summary, st) != hipSuccess)
         return KAN_ERR_HIP;
     int32_t span = 0;
@@ -132,27 +168,32 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     const int64_t n_o = (int64_t)K * d->n_out;
 
     const bool bwd = pass == KAN_PASS_BACKWARD;
-    float *hid = (float *)(ws + L.hid);
-    if (launch_cg_hidden(p->E, p->W1, p->b1, g_first, bwd ? (float *)(ws + L.z) : nullptr,
-                         bwd ? (float *)(ws + L.pre) : nullptr, hid, d->n_in, span, d->d_pe, d->d_feat,
+    out->g_first = g_first; out->cell_base = cell_base;
+    if (saved) {
+        const SavedLayout S = saved_layout(d, span);
+        out->hid = (float *)(saved + S.hid); out->cf = (float *)(saved + S.cf);
+        out->z = (float *)(saved + S.z); out->pre = (float *)(saved + S.pre); out->raw = (float *)(saved + S.raw);
+    } else {
+        out->hid = (float *)(ws + L.hid); out->cf = (float *)(ws + L.cf);
+        out->z = bwd ? (float *)(ws + L.z) : nullptr;
+        out->pre = bwd ? (float *)(ws + L.pre) : nullptr;
+        out->raw = bwd ? (float *)(ws + L.raw) : nullptr;
+    }
+    float *hid = out->hid;
+    if (launch_cg_hidden(p->E, p->W1, p->b1, g_first, out->z, out->pre, hid, d->n_in, span, d->d_pe, d->d_feat,
                          d->d_hidden, st) != hipSuccess)
         return KAN_ERR_HIP;
     GemmArgs a = {};
     a.A = hid; a.a_rs = d->d_hidden; a.a_cs = 1;
     a.B = p->W2; a.b_rs = n_o; a.b_cs = 1;
-    a.C = (float *)(ws + L.cf); a.ldc = n_o;
+    a.C = out->cf; a.ldc = n_o;
     a.M = rows; a.N = n_o; a.K = d->d_hidden;
     a.k_slice = d->d_hidden; a.c_slice = 0;
-    a.bias = p->b2; a.scale = p->scale; a.C2 = bwd ? (float *)(ws + L.raw) : nullptr;
+    a.bias = p->b2; a.scale = p->scale; a.C2 = out->raw;
     a.rows_per_input = span; a.n_out = d->n_out;
     if (launch_gemm(a, EPI_CG_OUT, 1, "cg_output_gemm", st) != hipSuccess) return KAN_ERR_HIP;
 
-    SplineGeom &g = out->g;
-    g.n_in = d->n_in; g.n_out = d->n_out;
-    g.rows = span * K; g.slab_rows = g.rows; g.k = d->k;
-    g.lo = 0.0f; g.inv_h = inv_h;
-    g.cell_base = cell_base;
-    g.base_act = d->base_act;
+    spline_geom(d, span, cell_base, &out->g);
     return KAN_OK;
 }
 
@@ -184,21 +225,86 @@ extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *desc, int64_t B, i
                        b_slices_for(desc, B, max_groups), pass).total;
 }
 
-extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
-                               float *y, int32_t max_groups, void *ws, size_t ws_bytes, void *stream)
+namespace {
+int forward_impl(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p, float *y,
+                 int32_t max_groups, void *ws, size_t ws_bytes, void *stream, char *saved, int32_t *span)
 {
     int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_FORWARD);
     if (rc != KAN_OK || B == 0) return rc;
     if (!y || ((uintptr_t)y % 16) != 0) return KAN_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     Prepared pr;
-    rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr);
+    rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr, saved);
     if (rc != KAN_OK) return rc;
-    const float *cf = (const float *)((char *)ws + pr.L.cf);
-    hipError_t e = narrow_applicable(pr.g) ? launch_forward_narrow(pr.g, x, cf, p->w_b, y, B, st)
-                                           : launch_forward_generic(pr.g, x, cf, p->w_b, y, B, st);
+    if (span) *span = pr.n_g;
+    hipError_t e = narrow_applicable(pr.g) ? launch_forward_narrow(pr.g, x, pr.cf, p->w_b, y, B, st)
+                                           : launch_forward_generic(pr.g, x, pr.cf, p->w_b, y, B, st);
     if (e != hipSuccess) return KAN_ERR_HIP;
     return KAN_OK;
+}
+
+int backward_body(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p, const float *gy,
+                  float *gx, const ukan_grads *g, int32_t max_groups, char *w, const Prepared &pr, hipStream_t st);
+
+int check_backward_args(const float *gy, const float *gx, const ukan_grads *g)
+{
+    if (!gy || ((uintptr_t)gy % 16) != 0 || ((uintptr_t)gx % 16) != 0) return KAN_ERR_INVALID_ARG;
+    if (g)
+        for (const void *q : {(const void *)g->gE, (const void *)g->gW1, (const void *)g->gb1, (const void *)g->gW2,
+                              (const void *)g->gb2, (const void *)g->gscale, (const void *)g->gw_b})
+            if (q && ((uintptr_t)q % 16) != 0) return KAN_ERR_INVALID_ARG;
+    return KAN_OK;
+}
+}  // namespace
+
+extern "C" int ukan_cg_forward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                               float *y, int32_t max_groups, void *ws, size_t ws_bytes, void *stream)
+{
+    return forward_impl(desc, B, x, p, y, max_groups, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+extern "C" size_t ukan_saved_bytes(const ukan_layer_desc *desc, int32_t max_groups)
+{
+    if (check_desc(desc) != KAN_OK || max_groups < 2) return 0;
+    return saved_layout(desc, max_groups).total;
+}
+
+extern "C" int ukan_cg_forward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                                     float *y, int32_t max_groups, void *saved, size_t saved_bytes, int32_t *span,
+                                     void *ws, size_t ws_bytes, void *stream)
+{
+    if (!span) return KAN_ERR_INVALID_ARG;
+    *span = 0;
+    const size_t need = ukan_saved_bytes(desc, max_groups);
+    if (need == 0) return check_desc(desc) != KAN_OK ? check_desc(desc) : KAN_ERR_INVALID_ARG;
+    if (B > 0 && (!saved || ((uintptr_t)saved % kAlign) != 0 || saved_bytes < need)) return KAN_ERR_WORKSPACE;
+    return forward_impl(desc, B, x, p, y, max_groups, ws, ws_bytes, stream, (char *)saved, span);
+}
+
+extern "C" int ukan_cg_backward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                                      const float *gy, float *gx, const ukan_grads *g, int32_t max_groups,
+                                      const void *saved, size_t saved_bytes, int32_t span, void *ws, size_t ws_bytes,
+                                      void *stream)
+{
+    int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_BACKWARD);
+    if (rc != KAN_OK || B == 0) return rc;
+    rc = check_backward_args(gy, gx, g);
+    if (rc != KAN_OK) return rc;
+    if (span < 2 || span > max_groups) return KAN_ERR_RANGE;
+    if (!saved || ((uintptr_t)saved % kAlign) != 0 || saved_bytes < ukan_saved_bytes(desc, max_groups))
+        return KAN_ERR_WORKSPACE;
+    char *sv = (char *)saved;      // read only below
+    Prepared pr;
+    pr.n_g = span;
+    pr.cp = chunks_for(desc, B, max_groups);
+    pr.L = make_layout(desc, B, span, pr.cp.n_chunks, record_bytes_for(desc, B, max_groups),
+                       b_slices_for(desc, B, max_groups), KAN_PASS_BACKWARD);
+    const SavedLayout S = saved_layout(desc, span);
+    pr.g_first = (int32_t *)(sv + S.g_first); pr.cell_base = (int32_t *)(sv + S.cell_base);
+    pr.hid = (float *)(sv + S.hid); pr.cf = (float *)(sv + S.cf);
+    pr.z = (float *)(sv + S.z); pr.pre = (float *)(sv + S.pre); pr.raw = (float *)(sv + S.raw);
+    spline_geom(desc, span, pr.cell_base, &pr.g);
+    return backward_body(desc, B, x, p, gy, gx, g, max_groups, (char *)ws, pr, (hipStream_t)stream);
 }
 
 extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
@@ -207,16 +313,20 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
 {
     int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_BACKWARD);
     if (rc != KAN_OK || B == 0) return rc;
-    if (!gy || ((uintptr_t)gy % 16) != 0 || ((uintptr_t)gx % 16) != 0) return KAN_ERR_INVALID_ARG;
-    if (g)
-        for (const void *q : {(const void *)g->gE, (const void *)g->gW1, (const void *)g->gb1, (const void *)g->gW2,
-                              (const void *)g->gb2, (const void *)g->gscale, (const void *)g->gw_b})
-            if (q && ((uintptr_t)q % 16) != 0) return KAN_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    char *w = (char *)ws;
-    Prepared pr;
-    rc = prepare(desc, B, x, p, max_groups, w, KAN_PASS_BACKWARD, st, &pr);
+    rc = check_backward_args(gy, gx, g);
     if (rc != KAN_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    Prepared pr;
+    rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_BACKWARD, st, &pr);
+    if (rc != KAN_OK) return rc;
+    return backward_body(desc, B, x, p, gy, gx, g, max_groups, (char *)ws, pr, st);
+}
+
+namespace {
+// steps after the coefficient table exists: dL/dx, the table gradient, and its way back through the CG
+int backward_body(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p, const float *gy,
+                  float *gx, const ukan_grads *g, int32_t max_groups, char *w, const Prepared &pr, hipStream_t st)
+{
     const Layout &L = pr.L;
     const int K = desc->k + 1, dh = desc->d_hidden, dz = desc->d_feat + desc->d_pe;
     const int64_t rows = (int64_t)desc->n_in * pr.n_g, n_o = (int64_t)K * desc->n_out;
@@ -225,8 +335,8 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     const WalkPlan wp = walk_for(desc, B, max_groups);
     const bool fused_dx = gx && wp.ok;      // dL/dx rides along with the table gradient
     if (gx && !fused_dx) {
-        hipError_t e = narrow ? launch_dx_narrow(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st)
-                              : launch_dx_generic(pr.g, x, (const float *)(w + L.cf), p->w_b, gy, gx, B, st);
+        hipError_t e = narrow ? launch_dx_narrow(pr.g, x, pr.cf, p->w_b, gy, gx, B, st)
+                              : launch_dx_generic(pr.g, x, pr.cf, p->w_b, gy, gx, B, st);
         if (e != hipSuccess) return KAN_ERR_HIP;
     }
 
@@ -240,7 +350,7 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     float *gout = (float *)(w + L.gout);
     int b_slices;
     if (wp.ok) {
-        if (launch_backward_walk(pr.g, wp, x, gy, (const float *)(w + L.cf), p->w_b, w + L.rec, fused_dx ? gx : nullptr,
+        if (launch_backward_walk(pr.g, wp, x, gy, pr.cf, p->w_b, w + L.rec, fused_dx ? gx : nullptr,
                                  want_params ? part_c : nullptr, want_b ? part_b : nullptr, B, st) != hipSuccess)
             return KAN_ERR_HIP;
         b_slices = pr.cp.n_chunks * wp.n_seg;
@@ -251,14 +361,14 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
         b_slices = pr.cp.n_chunks * dparam_generic_row_blocks(pr.g.rows);
     }
     if (!want_params) return KAN_OK;
-    if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, (const float *)(w + L.raw), p->scale,
+    if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, pr.raw, p->scale,
                              cg_grads ? gout : nullptr, g->gscale, g->gw_b, desc->n_in, pr.g.rows, desc->n_out,
                              pr.cp.n_chunks, b_slices, st) != hipSuccess)
         return KAN_ERR_HIP;
     if (!cg_grads) return KAN_OK;
 
     float *split = (float *)(w + L.split);
-    const float *hid = (const float *)(w + L.hid);
+    const float *hid = pr.hid;
     float *gpre = (float *)(w + L.gpre);
     const int slices = split_slices(rows);
     int64_t k_slice = (rows + slices - 1) / slices;
@@ -281,12 +391,12 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
         a.B = p->W2; a.b_rs = 1; a.b_cs = n_o;
         a.C = gpre; a.ldc = dh; a.M = rows; a.N = dh; a.K = n_o;
         a.k_slice = n_o; a.c_slice = 0;
-        a.aux = (const float *)(w + L.pre);
+        a.aux = pr.pre;
         if (launch_gemm(a, EPI_SILU_GRAD, 1, "cg_ghid_gemm", st) != hipSuccess) return KAN_ERR_HIP;
         if (g->gb1 && launch_colsum(gpre, split, g->gb1, rows, dh, st) != hipSuccess) return KAN_ERR_HIP;
         if (g->gW1) {   // gW1[p][c] = sum_rows z[row][p] * gpre[row][c]
             GemmArgs b = {};
-            b.A = (const float *)(w + L.z); b.a_rs = 1; b.a_cs = dz;
+            b.A = pr.z; b.a_rs = 1; b.a_cs = dz;
             b.B = gpre; b.b_rs = dh; b.b_cs = 1;
             b.C = split; b.ldc = dh; b.M = dz; b.N = dh; b.K = rows;
             b.k_slice = k_slice; b.c_slice = (int64_t)dz * dh;
@@ -300,6 +410,7 @@ extern "C" int ukan_cg_backward(const ukan_layer_desc *desc, int64_t B, const fl
     }
     return KAN_OK;
 }
+}  // namespace
 
 namespace {
 inline int64_t floordiv64(int64_t a, int64_t b) { int64_t q = a / b; return (a % b != 0 && ((a < 0) != (b < 0))) ? q - 1 : q; }

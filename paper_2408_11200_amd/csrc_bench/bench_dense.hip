@@ -5,11 +5,27 @@
 // it materialises Phi in the workspace and runs the contraction through rocBLAS on the matrix cores.
 // The backward pass is the same idea: gPhi = gy * C^T and gC = Phi^T * gy as two more GEMMs, dL/dx as
 // the row-wise product of gPhi with dPhi/dx.
+// This file belongs to the benchmark library (kan_bench.h); of the layer library it shares only the
+// header-only pair evaluation.
+#include <hip/hip_runtime.h>
 #include <rocblas/rocblas.h>
-#include "kan.h"
-#include "kan_launch.hpp"
+#include "kan_bench.h"
+#include "kan_device.hpp"
 
 namespace kan {
+
+// scale-folded table of the baseline: cf[i][m][j] = w_s[i][j] * coef[i][m][j] for m < rows, cf[i][rows][j] = w_b[i][j]
+__global__ __launch_bounds__(256) void dense_fold_kernel(const float *__restrict__ coef, const float *__restrict__ w_s,
+                                                         const float *__restrict__ w_b, float *__restrict__ cf,
+                                                         int n_in, int rows, int n_out)
+{
+    const int64_t per_in = (int64_t)(rows + 1) * n_out, total = (int64_t)n_in * per_in;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = p / per_in, rem = p - i * per_in;
+        const int64_t m = rem / n_out, j = rem % n_out;
+        cf[p] = m < rows ? coef[(i * rows + m) * n_out + j] * w_s[i * n_out + j] : (w_b ? w_b[i * n_out + j] : 0.0f);
+    }
+}
 
 // one thread per (sample, input): evaluate the pair and write its (rows + 1) entries of Phi
 __global__ __launch_bounds__(256) void dense_expand_kernel(SplineGeom g, const float *__restrict__ x,
@@ -91,6 +107,22 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 rocblas_handle g_handle = nullptr;
+
+// brackets one launch with the event pair of kan_profile_* (a no-op while profiling is off)
+struct Timed {
+    hipStream_t st;
+    Timed(const char *family, hipStream_t s) : st(s) { kan_profile_before(family, (void *)s); }
+    ~Timed() { kan_profile_after(nullptr, (void *)st); }
+};
+
+hipError_t fold(const float *coef, const float *w_s, const float *w_b, float *cf, int n_in, int rows, int n_out,
+                hipStream_t st)
+{
+    const int64_t want = ((int64_t)n_in * (rows + 1) * n_out + 255) / 256;
+    Timed tm("dense_fold", st);
+    dense_fold_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, st>>>(coef, w_s, w_b, cf, n_in, rows, n_out);
+    return hipGetLastError();
+}
 }  // namespace
 
 extern "C" size_t kan_dense_baseline_workspace_bytes(const kan_layer_desc *d, int64_t B)
@@ -118,10 +150,10 @@ extern "C" int kan_dense_baseline_forward(const kan_layer_desc *d, int64_t B, co
     const int64_t kd = (int64_t)g.n_in * g.slab_rows;
     float *cf = (float *)ws;
     float *phi = (float *)((char *)ws + align_up((size_t)kd * g.n_out * sizeof(float)));
-    if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess)
+    if (fold(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess)
         return KAN_ERR_HIP;
     {
-        prof::Timed tm("dense_expand", st);
+        Timed tm("dense_expand", st);
         const int64_t pairs = B * g.n_in;
         dense_expand_kernel<<<(unsigned)((pairs + 255) / 256), 256, 0, st>>>(g, x, phi, B);
         if (hipGetLastError() != hipSuccess) return KAN_ERR_HIP;
@@ -129,7 +161,7 @@ extern "C" int kan_dense_baseline_forward(const kan_layer_desc *d, int64_t B, co
     if (!g_handle && rocblas_create_handle(&g_handle) != rocblas_status_success) return KAN_ERR_HIP;
     if (rocblas_set_stream(g_handle, st) != rocblas_status_success) return KAN_ERR_HIP;
     const float one = 1.0f, zero = 0.0f;
-    prof::Timed tm("dense_gemm", st);
+    Timed tm("dense_gemm", st);
     // row-major y[B][n_out] = phi[B][kd] * cf[kd][n_out]  ==  column-major y^T = cf^T * phi^T
     rocblas_status rs = rocblas_sgemm(g_handle, rocblas_operation_none, rocblas_operation_none, g.n_out, (int)B,
                                       (int)kd, &one, cf, g.n_out, phi, (int)kd, &zero, y, g.n_out);
@@ -167,11 +199,11 @@ extern "C" int kan_dense_baseline_backward(const kan_layer_desc *d, int64_t B, c
     float *phi = (float *)at;  at += mat;
     float *dphi = (float *)at; at += mat;
     float *gphi = (float *)at;
-    if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess)
+    if (fold(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess)
         return KAN_ERR_HIP;
     const int64_t pairs = B * g.n_in;
     {
-        prof::Timed tm("dense_expand", st);
+        Timed tm("dense_expand", st);
         dense_expand_grad_kernel<<<(unsigned)((pairs + 255) / 256), 256, 0, st>>>(g, x, phi, dphi, B);
         if (hipGetLastError() != hipSuccess) return KAN_ERR_HIP;
     }
@@ -181,24 +213,24 @@ extern "C" int kan_dense_baseline_backward(const kan_layer_desc *d, int64_t B, c
     if (gx) {
         {
             // row-major gphi[B][kd] = gy[B][n_out] * cf[kd][n_out]^T  ==  column-major gphi^T = cf * gy^T
-            prof::Timed tm("dense_gemm", st);
+            Timed tm("dense_gemm", st);
             if (rocblas_sgemm(g_handle, rocblas_operation_transpose, rocblas_operation_none, (int)kd, (int)B, g.n_out,
                               &one, cf, g.n_out, gy, g.n_out, &zero, gphi, (int)kd) != rocblas_status_success)
                 return KAN_ERR_HIP;
         }
-        prof::Timed tm("dense_gx", st);
+        Timed tm("dense_gx", st);
         dense_gx_kernel<<<(unsigned)((pairs + 255) / 256), 256, 0, st>>>(gphi, dphi, gx, pairs, g.slab_rows);
         if (hipGetLastError() != hipSuccess) return KAN_ERR_HIP;
     }
     if (gcoef || gw_s || gw_b) {
         {
             // row-major gcf[kd][n_out] = phi[B][kd]^T * gy[B][n_out]  ==  column-major gcf^T = gy^T * phi
-            prof::Timed tm("dense_gemm", st);
+            Timed tm("dense_gemm", st);
             if (rocblas_sgemm(g_handle, rocblas_operation_none, rocblas_operation_transpose, g.n_out, (int)kd, (int)B,
                               &one, gy, g.n_out, phi, (int)kd, &zero, gcf, g.n_out) != rocblas_status_success)
                 return KAN_ERR_HIP;
         }
-        prof::Timed tm("dense_unfold", st);
+        Timed tm("dense_unfold", st);
         const int64_t edges = (int64_t)g.n_in * g.n_out;
         dense_unfold_kernel<<<(unsigned)((edges + 255) / 256), 256, 0, st>>>(gcf, coef, w_s, gcoef, gw_s, gw_b, g.n_in,
                                                                             g.rows, g.n_out, g.base_act ? 1 : 0);

@@ -1,17 +1,17 @@
-// Per-kernel event timing used by the benchmark (kan_profile_enable / kan_profile_read).
+// Per-kernel event timing for benchmarks (kan_bench.h): two launch hooks that bracket every kernel
+// launch of the layer library with a pair of HIP events, and the read-out of the totals per kernel
+// family.  This file belongs to the benchmark library, not to the layer library.
+#include <hip/hip_runtime.h>
 #include <string.h>
 #include <vector>
-#include "kan.h"
-#include "kan_launch.hpp"
-
-namespace kanprof {
+#include "kan_bench.h"
 
 namespace {
 struct Record { const char *family; hipEvent_t e0, e1; bool closed; };
 bool g_on = false;
 std::vector<Record> g_records;
 constexpr size_t kMaxRecords = 8192;
-bool g_open = false;     // a begin() without its end()
+bool g_open = false;     // a "before" without its "after"
 
 void clear()
 {
@@ -21,31 +21,27 @@ void clear()
 }
 }  // namespace
 
-bool enabled() { return g_on && g_records.size() < kMaxRecords; }
-
-void begin(const char *family, hipStream_t st)
+extern "C" void kan_profile_before(const char *family, void *stream)
 {
+    if (!g_on || g_records.size() >= kMaxRecords) return;
     Record r;
     r.family = family;
     r.closed = false;
     if (hipEventCreate(&r.e0) != hipSuccess) return;
     if (hipEventCreate(&r.e1) != hipSuccess) { (void)hipEventDestroy(r.e0); return; }
-    (void)hipEventRecord(r.e0, st);
+    (void)hipEventRecord(r.e0, (hipStream_t)stream);
     g_records.push_back(r);
     g_open = true;
 }
 
-void end(hipStream_t st)
+extern "C" void kan_profile_after(const char *family, void *stream)
 {
+    (void)family;
     if (!g_open || g_records.empty()) return;
-    (void)hipEventRecord(g_records.back().e1, st);
+    (void)hipEventRecord(g_records.back().e1, (hipStream_t)stream);
     g_records.back().closed = true;
     g_open = false;
 }
-
-}  // namespace kanprof
-
-using namespace kanprof;
 
 extern "C" int kan_profile_enable(int on)
 {

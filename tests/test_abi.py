@@ -1,4 +1,4 @@
-"""The C-ABI library loads without a GPU and exports every function include/kan.h declares."""
+"""The C-ABI libraries load without a GPU and export every function their headers declare."""
 import ctypes
 import os
 import re
@@ -17,8 +17,15 @@ def lib():
     return ctypes.CDLL(binding.LIB_PATH)
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "kan.h")).read()
+@pytest.fixture(scope="module")
+def bench_lib():
+    if not os.path.exists(binding.BENCH_LIB_PATH):
+        build.build()
+    return ctypes.CDLL(binding.BENCH_LIB_PATH)
+
+
+def declared_functions(header="kan.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
     return sorted({n for n in names if n.startswith(("kan_", "ukan_"))})
@@ -30,6 +37,28 @@ def test_every_declared_symbol_is_exported(lib):
     for n in names:
         assert hasattr(lib, n), n
     assert set(binding.EXPORTS) == set(names)
+
+
+def test_bench_library_exports_its_header(bench_lib, lib):
+    names = declared_functions("kan_bench.h")
+    assert {"kan_profile_enable", "kan_profile_read", "kan_dense_baseline_forward"} <= set(names)
+    for n in names:
+        assert hasattr(bench_lib, n), n
+        assert not hasattr(lib, n), n + " belongs to the benchmark library only"
+    assert set(binding.BENCH_EXPORTS) == set(names)
+
+
+def test_layer_library_links_no_blas(lib):
+    """Only the benchmark library may depend on rocBLAS."""
+    import subprocess
+    needed = subprocess.run(["readelf", "-d", binding.LIB_PATH], stdout=subprocess.PIPE, text=True).stdout
+    assert "NEEDED" in needed and "blas" not in needed.lower()
+
+
+def test_launch_observer_is_host_only(lib):
+    lib.kan_set_launch_observer.restype = ctypes.c_int
+    lib.kan_set_launch_observer.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.kan_set_launch_observer(None, None) == binding.KAN_OK
 
 
 def test_host_only_calls(lib):

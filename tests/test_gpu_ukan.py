@@ -155,6 +155,59 @@ def test_ukan_range_error_and_arguments():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("B,n_in,n_out,base_act", [(700, 5, 64, 1), (3000, 12, 256, 0), (257, 9, 1, 0)])
+def test_ukan_saved_handoff_equals_recompute(B, n_in, n_out, base_act):
+    """ukan_cg_forward_saved + ukan_cg_backward_saved (the backward pass reuses the forward pass's span,
+    cell offsets, CG activations and table) give bit for bit what the self-contained pair gives, which
+    the tests above hold against the oracle."""
+    spec, p, x, gy = make(21, B, n_in, n_out, base_act=base_act)
+    pd = {n: dev(a) for n, a in p.items()}
+    xd, gyd = dev(x), dev(gy)
+    y_ref = binding.ukan_cg_forward(spec, xd, pd, 64)
+    g_ref = binding.ukan_cg_backward(spec, xd, pd, gyd, 64)
+    y, saved, span = binding.ukan_cg_forward_saved(spec, xd, pd, 64)
+    assert 2 <= span <= 64 and saved.numel() >= binding.ukan_saved_bytes(spec, 64)
+    # scribble over a workspace-sized buffer in between: the backward pass must depend on `saved` only
+    torch.empty(binding.ukan_workspace_bytes(spec, B, 64, binding.PASS_BACKWARD), dtype=torch.uint8,
+                device="cuda").fill_(0xAB)
+    g = binding.ukan_cg_backward_saved(spec, xd, pd, gyd, 64, saved, span)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_ref)
+    assert set(g) == set(g_ref)
+    for n in g:
+        assert torch.equal(g[n], g_ref[n]), n
+    inv_h = oracle.inv_h_of_spacing(spec.h)
+    ref = oracle.ukan_backward(x, p, gy, spec.k, inv_h, spec.base_act)
+    for name in ref:
+        assert_close(g[name], ref[name], GRAD_TOL, name)
+
+
+def test_ukan_saved_errors():
+    spec, p, x, gy = make(22, 64, 3, 8)
+    pd = {n: dev(a) for n, a in p.items()}
+    y, saved, span = binding.ukan_cg_forward_saved(spec, dev(x), pd, 16)
+    for bad_span in (1, 17):
+        with pytest.raises(binding.KanError) as e:
+            binding.ukan_cg_backward_saved(spec, dev(x), pd, dev(gy), 16, saved, bad_span)
+        assert e.value.status == binding.KAN_ERR_RANGE
+    with pytest.raises(binding.KanError) as e:
+        binding.ukan_cg_backward_saved(spec, dev(x), pd, dev(gy), 16, saved[:256], span)
+    assert e.value.status == binding.KAN_ERR_WORKSPACE
+    # an outlier sample widens one input's span beyond max_groups: the call reports it and writes no y
+    x[5, 1] = 500.0
+    y = torch.full((64, 8), 7.0, device="cuda")
+    with pytest.raises(binding.KanError) as e:
+        binding.ukan_cg_forward_saved(spec, dev(x), pd, 16, y=y)
+    assert e.value.status == binding.KAN_ERR_RANGE
+    assert (y == 7.0).all()
+    # the caller's way out: a larger max_groups (here the outlier needs ~500 groups of width (k+1) h = 1)
+    y2, _, span2 = binding.ukan_cg_forward_saved(spec, dev(x), pd, 1024)
+    assert span2 > 16
+    inv_h = oracle.inv_h_of_spacing(spec.h)
+    assert_close(y2, oracle.ukan_forward(x, p, spec.k, inv_h, spec.base_act), FWD_TOL, "y with the outlier")
+    torch.cuda.synchronize()
+
+
 def test_ukan_backward_bit_reproducible():
     spec, p, x, gy = make(9, 2000, 12, 128)
     pd = {n: dev(a) for n, a in p.items()}

@@ -178,9 +178,18 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _workspace(nbytes, device):
+def _on_stream(t, stream):
+    """A tensor allocated here (on torch's current stream) but used by work enqueued on another
+    stream: tell the caching allocator, so the block is not handed out again, once the Python
+    object is gone, before that work has finished."""
+    if stream is not None and t.numel():
+        t.record_stream(stream)
+    return t
+
+
+def _workspace(nbytes, device, stream=None):
     # torch's allocator hands out 512-byte aligned blocks
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    return _on_stream(torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device), stream)
 
 
 def kan_workspace_bytes(spec, B, which=PASS_FORWARD):
@@ -193,9 +202,9 @@ def kan_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=None):
     d = kan_desc(spec)
     B = x.shape[0]
     if y is None:
-        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+        y = _on_stream(torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device), stream)
     if ws is None:
-        ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_FORWARD), x.device)
+        ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_FORWARD), x.device, stream)
     rc = lib.kan_forward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(y),
                          _ptr(ws), ws.numel(), _stream(stream))
     if rc != KAN_OK:
@@ -227,9 +236,9 @@ def kan_backward(spec, x, coef, w_s, w_b, gy, want=("gx", "gcoef", "gw_s", "gw_b
     out = dict(out or {})
     for name in want:
         if name not in out:
-            out[name] = torch.empty(shapes[name], dtype=torch.float32, device=x.device)
+            out[name] = _on_stream(torch.empty(shapes[name], dtype=torch.float32, device=x.device), stream)
     if ws is None:
-        ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_BACKWARD), x.device)
+        ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_BACKWARD), x.device, stream)
     rc = lib.kan_backward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
                           _f32(out.get("gx")), _f32(out.get("gcoef")), _f32(out.get("gw_s")),
                           _f32(out.get("gw_b")), _ptr(ws), ws.numel(), _stream(stream))
@@ -241,7 +250,7 @@ def kan_backward(spec, x, coef, w_s, w_b, gy, want=("gx", "gcoef", "gw_s", "gw_b
 def kan_interval_index(spec, x, stream=None):
     lib = load()
     d = kan_desc(spec)
-    idx = torch.empty(x.shape, dtype=torch.int32, device=x.device)
+    idx = _on_stream(torch.empty(x.shape, dtype=torch.int32, device=x.device), stream)
     rc = lib.kan_interval_index(ctypes.byref(d), x.numel(), _f32(x), _ptr(idx), _stream(stream))
     if rc != KAN_OK:
         raise KanError(rc, "kan_interval_index")
@@ -261,9 +270,9 @@ def kan_dense_baseline_forward(spec, x, coef, w_s, w_b, y=None, ws=None, stream=
     d = kan_desc(spec)
     B = x.shape[0]
     if y is None:
-        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+        y = _on_stream(torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device), stream)
     if ws is None:
-        ws = _workspace(lib.kan_dense_baseline_workspace_bytes(ctypes.byref(d), B), x.device)
+        ws = _workspace(lib.kan_dense_baseline_workspace_bytes(ctypes.byref(d), B), x.device, stream)
     rc = lib.kan_dense_baseline_forward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(y),
                                         _ptr(ws), ws.numel(), _stream(stream))
     if rc != KAN_OK:
@@ -281,9 +290,9 @@ def kan_dense_baseline_backward(spec, x, coef, w_s, w_b, gy, out=None, ws=None, 
     out = dict(out or {})
     for name in shapes:
         if name not in out:
-            out[name] = torch.empty(shapes[name], dtype=torch.float32, device=x.device)
+            out[name] = _on_stream(torch.empty(shapes[name], dtype=torch.float32, device=x.device), stream)
     if ws is None:
-        ws = _workspace(lib.kan_dense_baseline_backward_workspace_bytes(ctypes.byref(d), B), x.device)
+        ws = _workspace(lib.kan_dense_baseline_backward_workspace_bytes(ctypes.byref(d), B), x.device, stream)
     rc = lib.kan_dense_baseline_backward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
                                          _f32(out["gx"]), _f32(out["gcoef"]), _f32(out["gw_s"]), _f32(out["gw_b"]),
                                          _ptr(ws), ws.numel(), _stream(stream))
@@ -339,9 +348,9 @@ def ukan_cg_forward(spec, x, p, max_groups, y=None, ws=None, stream=None):
     d = ukan_desc(spec)
     B = x.shape[0]
     if y is None:
-        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+        y = _on_stream(torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device), stream)
     if ws is None:
-        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_FORWARD), x.device)
+        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_FORWARD), x.device, stream)
     pp = _ukan_params(p)
     rc = lib.ukan_cg_forward(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(y), max_groups, _ptr(ws),
                              ws.numel(), _stream(stream))
@@ -361,11 +370,11 @@ def ukan_cg_forward_saved(spec, x, p, max_groups, saved=None, y=None, ws=None, s
     d = ukan_desc(spec)
     B = x.shape[0]
     if y is None:
-        y = torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device)
+        y = _on_stream(torch.empty((B, spec.n_out), dtype=torch.float32, device=x.device), stream)
     if saved is None:
-        saved = _workspace(lib.ukan_saved_bytes(ctypes.byref(d), max_groups), x.device)
+        saved = _workspace(lib.ukan_saved_bytes(ctypes.byref(d), max_groups), x.device, stream)
     if ws is None:
-        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_FORWARD), x.device)
+        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_FORWARD), x.device, stream)
     pp = _ukan_params(p)
     span = ctypes.c_int32(0)
     rc = lib.ukan_cg_forward_saved(ctypes.byref(d), B, _f32(x), ctypes.byref(pp), _f32(y), max_groups, _ptr(saved),
@@ -389,9 +398,9 @@ def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, s
     if want is None:
         want = [n for n in shapes if n != "gw_b" or spec.base_act]
     if out is None:
-        out = {n: torch.empty(shapes[n], dtype=torch.float32, device=x.device) for n in want}
+        out = {n: _on_stream(torch.empty(shapes[n], dtype=torch.float32, device=x.device), stream) for n in want}
     if ws is None:
-        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_BACKWARD), x.device)
+        ws = _workspace(lib.ukan_workspace_bytes(ctypes.byref(d), B, max_groups, PASS_BACKWARD), x.device, stream)
     pp = _ukan_params(p)
     gg = UkanGrads(*[(out[n].data_ptr() if n in out else None)
                      for n in ("gE", "gW1", "gb1", "gW2", "gb2", "gscale", "gw_b")])
@@ -418,10 +427,10 @@ def ukan_materialize(spec, p, cell_lo, cell_hi, coef=None, ws=None, stream=None)
     d = ukan_desc(spec)
     dev = p["E"].device
     if coef is None:
-        coef = torch.empty((spec.n_in, int(cell_hi) - int(cell_lo) + 1 + spec.k, spec.n_out), dtype=torch.float32,
-                           device=dev)
+        coef = _on_stream(torch.empty((spec.n_in, int(cell_hi) - int(cell_lo) + 1 + spec.k, spec.n_out),
+                                      dtype=torch.float32, device=dev), stream)
     if ws is None:
-        ws = _workspace(lib.ukan_materialize_workspace_bytes(ctypes.byref(d), int(cell_lo), int(cell_hi)), dev)
+        ws = _workspace(lib.ukan_materialize_workspace_bytes(ctypes.byref(d), int(cell_lo), int(cell_hi)), dev, stream)
     pp = _ukan_params(p)
     rc = lib.ukan_materialize(ctypes.byref(d), ctypes.byref(pp), int(cell_lo), int(cell_hi), _f32(coef), _ptr(ws),
                               ws.numel(), _stream(stream))
@@ -433,7 +442,7 @@ def ukan_materialize(spec, p, cell_lo, cell_hi, coef=None, ws=None, stream=None)
 def ukan_group_index(spec, x, stream=None):
     lib = load()
     d = ukan_desc(spec)
-    outs = [torch.empty(x.shape, dtype=torch.int32, device=x.device) for _ in range(3)]
+    outs = [_on_stream(torch.empty(x.shape, dtype=torch.int32, device=x.device), stream) for _ in range(3)]
     rc = lib.ukan_group_index(ctypes.byref(d), x.numel(), _f32(x), _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]),
                               _stream(stream))
     if rc != KAN_OK:

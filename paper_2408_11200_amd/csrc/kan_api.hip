@@ -32,6 +32,7 @@ int check_desc(const kan_layer_desc *d)
     if (d->n_in <= 0 || d->n_out <= 0 || d->G <= 0) return KAN_ERR_INVALID_ARG;
     if (!(d->grid_hi > d->grid_lo)) return KAN_ERR_INVALID_ARG;
     if (d->k < 1 || d->k > 5) return KAN_ERR_UNSUPPORTED;
+    if (d->n_in > 65535) return KAN_ERR_UNSUPPORTED;          // inputs index a 16-bit launch dimension
     if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
     return KAN_OK;
 }

@@ -294,9 +294,10 @@ __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const 
     constexpr int TJ = kWave * R;
     __shared__ float acc[kRowBlock * TJ];
     const int lane = threadIdx.x;
-    const int i = blockIdx.x;
-    const int jt = blockIdx.y % n_jt, rb = blockIdx.y / n_jt;
-    const int n_rb = gridDim.y / n_jt;
+    // grid.x carries (row block, output tile): it may exceed the 65535 limit of grid.y for long tables
+    const int i = blockIdx.y;
+    const int jt = blockIdx.x % n_jt, rb = blockIdx.x / n_jt;
+    const int n_rb = gridDim.x / n_jt;
     const int lo = rb * kRowBlock;
     const int hi = (lo + kRowBlock < g.rows) ? lo + kRowBlock : g.rows;
     const int j = jt * TJ + lane * R;
@@ -566,7 +567,8 @@ hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const floa
     const int R = pick_r(g.n_out);
     const int n_jt = (g.n_out + 64 * R - 1) / (64 * R);
     const int n_rb = dparam_generic_row_blocks(g.rows);
-    dim3 grid((unsigned)g.n_in, (unsigned)(n_jt * n_rb), (unsigned)n_chunks);
+    if (g.n_in > 65535 || n_chunks > 65535) return hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)(n_jt * n_rb), (unsigned)g.n_in, (unsigned)n_chunks);
     prof::Timed tm("dparam_generic", st);
     switch (R) {
     case 4: dparam_generic_kernel<4><<<grid, 64, 0, st>>>(g, x, gy, part_c, part_b, B, chunk_len, n_jt); break;

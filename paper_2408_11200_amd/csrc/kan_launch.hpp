@@ -28,6 +28,21 @@ namespace KAN_NS {
 
 namespace prof = ::kanprof;
 
+// Raises a kernel's dynamic LDS limit to `bytes` once per (kernel, device) instead of on every launch.
+// `Tag` is any type unique to the kernel instantiation (each gets its own table).
+template <typename Tag>
+inline hipError_t ensure_dynamic_lds(const void *kern, int bytes)
+{
+    static int have[64] = {};      // bytes already granted, per device ordinal
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && __atomic_load_n(&have[dev], __ATOMIC_ACQUIRE) >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) __atomic_store_n(&have[dev], bytes, __ATOMIC_RELEASE);
+    return e;
+}
+
 hipError_t launch_interval_index(const float *x, int32_t *idx, int64_t n, float lo, float inv_h,
                                  hipStream_t st);
 hipError_t launch_fold_scale(const float *coef, const float *w_s, const float *w_b, float *cf, int n_in, int rows,

@@ -363,8 +363,9 @@ static hipError_t forward_pairs_launch(const SplineGeom &g, const float *x, cons
     const size_t lds = 2ull * NQ * 64 * NW * 16 + (size_t)NW * 64 * 8 * sizeof(float);
     const bool mask = (g.n_out % (64 * R)) != 0 || (int64_t)g.slab_rows * (64 * R / 4) != (int64_t)NQ * 64 * NW;
     auto kern = mask ? forward_pairs_kernel<R, T, NW, NQ, true> : forward_pairs_kernel<R, T, NW, NQ, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    struct Masked; struct Plain;
+    hipError_t e = mask ? ensure_dynamic_lds<Masked>(reinterpret_cast<const void *>(kern), (int)lds)
+                        : ensure_dynamic_lds<Plain>(reinterpret_cast<const void *>(kern), (int)lds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((B + NW * T - 1) / (NW * T)), (unsigned)((g.n_out + 64 * R - 1) / (64 * R)));
     prof::Timed tm("forward_pairs", st);
@@ -380,8 +381,9 @@ static hipError_t forward_lds_launch(const SplineGeom &g, const float *x, const 
     // masking is needed only when some quad of the padded slab is not a real element
     const bool mask = (g.n_out % (64 * R)) != 0 || (int64_t)g.slab_rows * (64 * R / 4) != (int64_t)NQ * 64 * NW;
     auto kern = mask ? forward_lds_kernel<R, T, NW, NQ, true> : forward_lds_kernel<R, T, NW, NQ, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    struct Masked; struct Plain;
+    hipError_t e = mask ? ensure_dynamic_lds<Masked>(reinterpret_cast<const void *>(kern), (int)lds)
+                        : ensure_dynamic_lds<Plain>(reinterpret_cast<const void *>(kern), (int)lds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((B + NW * T - 1) / (NW * T)), (unsigned)((g.n_out + 64 * R - 1) / (64 * R)));
     prof::Timed tm("forward_lds", st);

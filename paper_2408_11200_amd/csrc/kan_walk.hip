@@ -324,8 +324,9 @@ hipError_t launch_sorted_records(const SplineGeom &g, const float *x, float *xT,
     const size_t lds = (size_t)S * 12;
     // long chunks: 16 waves per sort (one workgroup per CU fits anyway), short ones 4
     auto kern = S >= 4096 ? cell_sort_kernel<16> : cell_sort_kernel<4>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    struct Long; struct Short;
+    hipError_t e = S >= 4096 ? ensure_dynamic_lds<Long>(reinterpret_cast<const void *>(kern), (int)lds)
+                             : ensure_dynamic_lds<Short>(reinterpret_cast<const void *>(kern), (int)lds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((B + S - 1) / S), (unsigned)g.n_in);
     prof::Timed tm("walk_sort", st);

@@ -19,6 +19,7 @@ int check_desc(const ukan_layer_desc *d)
     if (d->n_in <= 0 || d->n_out <= 0 || !(d->h > 0.0f)) return KAN_ERR_INVALID_ARG;
     if (d->d_pe <= 0 || d->d_feat < 0 || d->d_hidden <= 0) return KAN_ERR_INVALID_ARG;
     if (d->k < 1 || d->k > 3) return KAN_ERR_UNSUPPORTED;
+    if (d->n_in > 65535) return KAN_ERR_UNSUPPORTED;          // inputs index a 16-bit launch dimension
     if (d->d_pe % 2 != 0) return KAN_ERR_UNSUPPORTED;         // sin/cos pairs
     if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
     return KAN_OK;

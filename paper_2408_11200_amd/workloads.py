@@ -171,3 +171,24 @@ def paper_shape(G, seed=1100, B=1 << 17, k=3):
     p = kan_params(rng, spec, 0.1, w_s_std=1.0 / np.sqrt(32), w_b_std=1.0 / np.sqrt(32))
     gy = _f32(rng.standard_normal((B, 32)))
     return Workload("P KAN 32->32 G%d k%d B%d" % (G, k, B), B, [spec], x, [p], gy)
+
+
+def regression_task(which, seed=1200, B=4096):
+    """Inputs and closed-form targets of the regression experiments (section "Tasks", functions I-III):
+    x uniform on [-1, 1]^d, d = 2 for I and II and 16 for III.  The targets are data for the training
+    loop, evaluated here in fp64 with library routines; they are no part of the layer's arithmetic.
+      I    exp(J0(20 x0) + x1^2)           (J0: Bessel function of the first kind, order 0)
+      II   exp(sin(pi x0) + x1^2)
+      III  exp((1/15) sum_{i=0..15} sin((4 i / 15 + 1) pi x_i))"""
+    from scipy.special import j0
+    rng = np.random.default_rng(seed + {"I": 1, "II": 2, "III": 3}[which])
+    d = 16 if which == "III" else 2
+    x = rng.uniform(-1.0, 1.0, size=(B, d))
+    if which == "I":
+        t = np.exp(j0(20.0 * x[:, 0]) + x[:, 1] ** 2)
+    elif which == "II":
+        t = np.exp(np.sin(np.pi * x[:, 0]) + x[:, 1] ** 2)
+    else:
+        i = np.arange(16)
+        t = np.exp(np.sin((4.0 * i / 15.0 + 1.0) * np.pi * x).sum(1) / 15.0)
+    return _f32(x), _f32(t[:, None])

@@ -199,6 +199,41 @@ def test_forward_local_equals_dense_definition(k, shape):
     assert (idx >= s.G + k).any() or (idx < -k).any()
 
 
+@pytest.mark.parametrize("k,n_in,n_out,G", [(3, 3, 5, 7), (2, 4, 2, 6), (1, 2, 3, 5), (4, 3, 2, 6)])
+def test_forward_and_backward_equal_einsum_over_library_basis(k, n_in, n_out, G):
+    """The layer written as one contraction over a basis tensor that comes from scipy, not from the oracle:
+    Phi[b][i][m] = B_{m,k}(x[b][i]) by BSpline.basis_element on the extended knots, then
+    y = einsum(Phi, coef, w_s) + silu(x) w_b with coefficients that differ along every axis and three
+    unequal extents (n_in, G + k, n_out), so a swapped or transposed index of coef[i][m][j], w_s[i][j] or
+    w_b[i][j] changes the result; the four gradients are the matching contractions with gy."""
+    lo, hi = -1.0, 1.5
+    assert len({n_in, G + k, n_out}) == 3
+    inv_h = oracle.inv_h_of(lo, hi, G)
+    tau = knots(G, k, lo, inv_h)
+    rng = np.random.default_rng(40 + k)
+    B = 37
+    x = np.float32(rng.uniform(lo - 0.3, hi + 0.3, (B, n_in)))          # some samples in the padding cells
+    coef = rng.standard_normal((n_in, G + k, n_out))
+    w_s = rng.standard_normal((n_in, n_out))
+    w_b = rng.standard_normal((n_in, n_out))
+    gy = rng.standard_normal((B, n_out))
+    els = [BSpline.basis_element(tau[m:m + k + 2], extrapolate=False) for m in range(G + k)]
+    x64 = x.astype(np.float64)
+    Phi = np.stack([np.nan_to_num(el(x64)) for el in els], axis=-1)                     # [B][n_in][G+k]
+    dPhi = np.stack([np.nan_to_num(el.derivative()(x64)) for el in els], axis=-1)
+    sig = expit(x64)
+    silu, dsilu = x64 * sig, sig * (1.0 + x64 * (1.0 - sig))
+    y_ref = np.einsum("bim,imj,ij->bj", Phi, coef, w_s) + silu @ w_b
+    y = oracle.kan_forward(x, coef, w_s, w_b, G, k, lo, inv_h)
+    np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-11)
+    g = oracle.kan_backward(x, coef, w_s, w_b, gy, G, k, lo, inv_h)
+    np.testing.assert_allclose(g["gcoef"], np.einsum("bim,bj,ij->imj", Phi, gy, w_s), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(g["gw_s"], np.einsum("bim,imj,bj->ij", Phi, coef, gy), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(g["gw_b"], silu.T @ gy, rtol=0, atol=1e-11)
+    gx_ref = np.einsum("bim,imj,ij,bj->bi", dPhi, coef, w_s, gy) + dsilu * (gy @ w_b.T)
+    np.testing.assert_allclose(g["gx"], gx_ref, rtol=0, atol=1e-10)
+
+
 def test_forward_constant_coefficients_reproduce_constant():
     """coef == c  =>  spline == c inside the grid, so y = sum_i (w_s*c + w_b*silu(x_i))."""
     w = _tiny(seed=21, outside=0.0, B=50, n_in=4, n_out=3, G=8, k=3)

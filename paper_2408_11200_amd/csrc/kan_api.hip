@@ -33,6 +33,8 @@ int check_desc(const kan_layer_desc *d)
     if (!(d->grid_hi > d->grid_lo)) return KAN_ERR_INVALID_ARG;
     if (d->k < 1 || d->k > 5) return KAN_ERR_UNSUPPORTED;
     if (d->n_in > 65535) return KAN_ERR_UNSUPPORTED;          // inputs index a 16-bit launch dimension
+    // float offsets inside one input's table are 32-bit
+    if (((int64_t)d->G + d->k + 1) * (int64_t)d->n_out >= (1ll << 31)) return KAN_ERR_UNSUPPORTED;
     if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
     return KAN_OK;
 }
@@ -82,21 +84,27 @@ struct BackwardPlan {
     ChunkPlan cp;
     size_t rec_bytes;       // transposed x + sorted records of the walk (0 for the generic kernel)
     int b_slices_per_chunk; // base-term partial slices each chunk writes
+    int n_slabs;            // partial slabs of the table gradient (one per chunk, or one shared by all)
+    size_t tail_bytes;      // scratch behind a single shared slab for the row-slice sums of gw_s
 };
 
 BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
 {
     SplineGeom g = geom_of(d);
     BackwardPlan bp;
-    bp.wp = plan_walk(g, B);
+    bp.wp = plan_walk(g, B, true);
     bp.walk = bp.wp.ok != 0 && !high_degree(d);
+    bp.tail_bytes = 0;
     if (bp.walk) {
+        bp.n_slabs = bp.wp.n_slabs;
+        if (bp.wp.shared) bp.tail_bytes = align_up(dparam_reduce_tail_bytes(g.n_in, g.n_out));
         bp.cp.n_chunks = bp.wp.n_chunks;
         bp.cp.chunk_len = bp.wp.S;
         bp.rec_bytes = align_up(walk_scratch_bytes(bp.wp, B, g.n_in, g.n_out));
         bp.b_slices_per_chunk = bp.wp.n_seg;
     } else {
         bp.cp = plan_chunks(B, g.n_in, g.rows, g.n_out);
+        bp.n_slabs = bp.cp.n_chunks;
         bp.rec_bytes = 0;
         bp.b_slices_per_chunk = high_degree(d) ? highk_row_blocks(g.rows) : dparam_generic_row_blocks(g.rows);
     }
@@ -124,7 +132,7 @@ extern "C" size_t kan_workspace_bytes(const kan_layer_desc *desc, int64_t B, int
     if (pass == KAN_PASS_FORWARD) return folded_bytes(desc);
     if (pass != KAN_PASS_BACKWARD) return 0;
     const BackwardPlan bp = backward_plan(desc, B);
-    return folded_bytes(desc) + bp.rec_bytes + (size_t)bp.cp.n_chunks * folded_bytes(desc) +
+    return folded_bytes(desc) + bp.rec_bytes + (size_t)bp.n_slabs * folded_bytes(desc) + bp.tail_bytes +
            (size_t)bp.cp.n_chunks * bp.b_slices_per_chunk * edge_bytes(desc);
 }
 
@@ -225,7 +233,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     const BackwardPlan bp = backward_plan(desc, B);
     if (high_degree(desc)) {
         float *part_c = (float *)((char *)ws + folded_bytes(desc));
-        float *part_b = (float *)((char *)part_c + (size_t)bp.cp.n_chunks * folded_bytes(desc));
+        float *part_b = (float *)((char *)part_c + (size_t)bp.n_slabs * folded_bytes(desc));
         return highk_backward(highk_of(desc), x, coef, w_s, w_b, gy, cf, gx, gcoef, gw_s, gw_b, part_c, part_b,
                               bp.cp.n_chunks, bp.cp.chunk_len, B, st) == hipSuccess
                    ? KAN_OK
@@ -249,7 +257,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         void *walk_scratch = at;
         at += bp.rec_bytes;
         float *part_c = (float *)at;
-        float *part_b = (float *)((char *)part_c + (size_t)cp.n_chunks * folded_bytes(desc));
+        float *part_b = (float *)((char *)part_c + (size_t)bp.n_slabs * folded_bytes(desc) + bp.tail_bytes);
         // partial slabs are laid out back to back with the unpadded slab size
         hipError_t e = bp.walk ? launch_backward_walk(g, bp.wp, x, gy, cf, w_b, walk_scratch, fused_dx ? gx : nullptr,
                                                       want_params ? part_c : nullptr, want_b ? part_b : nullptr, B, st)
@@ -258,7 +266,9 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         if (e != hipSuccess) return KAN_ERR_HIP;
         if (want_params &&
             launch_dparam_reduce(part_c, want_b ? part_b : nullptr, coef, w_s, gcoef, gw_s, gw_b, g.n_in, g.rows,
-                                 g.n_out, cp.n_chunks, cp.n_chunks * bp.b_slices_per_chunk, st) != hipSuccess)
+                                 g.n_out, bp.n_slabs, cp.n_chunks * bp.b_slices_per_chunk, st,
+                                 // a shared slab is followed by the folded table's spare row and the tail scratch
+                                 bp.tail_bytes ? bp.tail_bytes + (folded_bytes(desc) - (size_t)g.n_in * g.rows * g.n_out * sizeof(float)) : 0) != hipSuccess)
             return KAN_ERR_HIP;
     }
     return KAN_OK;

@@ -578,9 +578,11 @@ hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const floa
     return hipGetLastError();
 }
 
+size_t dparam_reduce_tail_bytes(int n_in, int n_out) { return 64 * (size_t)n_in * n_out * sizeof(double) + 8; }
+
 hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float *coef, const float *w_s,
                                 float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
-                                int n_chunks, int n_slices_b, hipStream_t st)
+                                int n_chunks, int n_slices_b, hipStream_t st, size_t tail_scratch)
 {
     const int64_t slab = (int64_t)n_in * rows * n_out, edges = (int64_t)n_in * n_out;
     const bool vec4 = n_out % 4 == 0 && ((uintptr_t)part_c % 16) == 0 && (!gcoef || ((uintptr_t)gcoef % 16) == 0) &&
@@ -596,10 +598,11 @@ hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float 
     }
     if (gw_s || gw_b) {
         // Long tables: the row sum behind gw_s is cut into row slices.  Their fp64 block sums live in
-        // the second chunk's partial slab, which is dead once the chunks have been summed.
+        // the second chunk's partial slab, which is dead once the chunks have been summed (or in the
+        // scratch the caller left behind a single slab).
         int n_rs = 1;
         double *slice_sums = nullptr;
-        if (gw_s && n_chunks >= 2 && rows >= 512) {
+        if (gw_s && (n_chunks >= 2 || tail_scratch >= dparam_reduce_tail_bytes(n_in, n_out)) && rows >= 512) {
             n_rs = rows / 256 < 64 ? rows / 256 : 64;
             slice_sums = (double *)(((uintptr_t)(part_c + slab) + 7) & ~(uintptr_t)7);
         }

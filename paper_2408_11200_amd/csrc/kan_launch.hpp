@@ -56,9 +56,12 @@ hipError_t launch_dx_generic(const SplineGeom &g, const float *x, const float *c
 int dparam_generic_row_blocks(int rows);     // base-term partial slices per chunk
 hipError_t launch_dparam_generic(const SplineGeom &g, const float *x, const float *gy, float *part_c,
                                  float *part_b, int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
+// tail_scratch: bytes of scratch that follow the first partial slab when there is only one (with two
+// or more, the second slab serves); 0 = none
+size_t dparam_reduce_tail_bytes(int n_in, int n_out);
 hipError_t launch_dparam_reduce(float *part_c, const float *part_b, const float *coef, const float *w_s,
                                 float *gcoef, float *gw_s, float *gw_b, int n_in, int rows, int n_out,
-                                int n_chunks, int n_slices_b, hipStream_t st);
+                                int n_chunks, int n_slices_b, hipStream_t st, size_t tail_scratch = 0);
 
 // narrow layers (n_out <= 16)
 int narrow_applicable(const SplineGeom &g);
@@ -79,8 +82,11 @@ hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *
 
 // Sorted pair records of the walk, one per (sample, input) pair, as a structure of arrays indexed
 // [chunk][input][rank in the chunk's sorted order]: first row of the K-wide window (clamped into the
-// table) | the sample's index inside its chunk << 16; the base value; the K window weights (16-byte
+// table; kRtRowBits bits) | the sample's index inside its chunk << kRtRowBits (chunks hold at most
+// 2^13 samples); the base value; the K window weights (16-byte
 // aligned quadruples); and the same for the x-derivatives (null when dL/dx is not wanted).
+constexpr int kRtRowBits = 19;
+constexpr int kRtRowMask = (1 << kRtRowBits) - 1;
 struct WalkRecords {
     int *rt;
     float *base;
@@ -101,8 +107,12 @@ struct WalkPlan {
     int streams, T;      // streams per wave, outputs per lane
     int n_jt;            // output tiles of (64 / streams) * T outputs
     int row_bits;        // bits of the largest window row (sort key width)
+    int shared;          // 1: one partial slab for all chunks, which are walked one after the other
+    int n_slabs;         // partial slabs the walk writes: n_chunks, or 1 when shared
 };
-WalkPlan plan_walk(const SplineGeom &g, int64_t B);
+// allow_shared: tables whose per-chunk partial slabs would not fit the budget are still planned, with the
+// chunks taking turns on a single slab (ok stays 0 for them otherwise).
+WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared = false);
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out);
 hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,
                                 const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,

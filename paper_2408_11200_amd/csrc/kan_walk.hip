@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * NW) void cell_sort_kernel(SplineGeom g, const 
             }
             wr[q] = v; dwr[q] = dv;
         }
-        rec.rt[list + p] = row0 | ((live ? e : 0) << 16);
+        rec.rt[list + p] = row0 | ((live ? e : 0) << kRtRowBits);
         rec.base[list + p] = base;
         *reinterpret_cast<float4 *>(rec.w4 + (list + p) * 4) = make_float4(wr[0], wr[1], wr[2], wr[3]);
         if (rec.dw4) {
@@ -192,16 +192,17 @@ __global__ __launch_bounds__(64 * NW) void cell_sort_kernel(SplineGeom g, const 
 // per (chunk, input, output).
 __global__ __launch_bounds__(256) void walk_carry_kernel(SplineGeom g, const int *__restrict__ rt,
                                                          const float *__restrict__ carry, float *__restrict__ part_c,
-                                                         int S, int n_chunks, int n_seg)
+                                                         int S, int n_chunks, int n_seg, int chunk0, int shared)
 {
+    // n_chunks chunks starting at chunk0 of the batch; shared: they all add to the one slab
     const int64_t at = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (at >= (int64_t)n_chunks * g.n_in * g.n_out) return;
     const int j = (int)(at % g.n_out);
-    const int64_t ci = at / g.n_out;               // chunk * n_in + input
+    const int64_t ci = (int64_t)chunk0 * g.n_in + at / g.n_out;               // chunk * n_in + input
     const int seg_len = S / n_seg;
-    float *slab = part_c + ci * g.rows * g.n_out + j;
+    float *slab = part_c + (shared ? ci % g.n_in : ci) * g.rows * g.n_out + j;
     for (int k = 1; k < n_seg; ++k) {
-        const int rf = rt[ci * S + (int64_t)k * seg_len] & 0xffff;
+        const int rf = rt[ci * S + (int64_t)k * seg_len] & kRtRowMask;
         const float *cr = carry + ((ci * n_seg + k) * kMaxK) * g.n_out + j;
         for (int s = 0; s < kMaxK; ++s)
             if (rf + s < g.rows) slab[(int64_t)(rf + s) * g.n_out] += cr[(int64_t)s * g.n_out];
@@ -236,10 +237,10 @@ int log2_exact(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
 
 // ---- planning and launch ---------------------------------------------------------------------
 
-WalkPlan plan_walk(const SplineGeom &g, int64_t B)
+WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared)
 {
     WalkPlan p = {};
-    if (g.rows < kMaxK || g.rows > 0xffff || B < 1) return p;
+    if (g.rows < kMaxK || g.rows > kRtRowMask || B < 1) return p;
     if (g.n_out % 8 == 0 && g.n_out > 256) {
         p.T = 8;            // one tile covers 512 outputs: the per-record work is shared by twice as many
         p.streams = 1;
@@ -278,6 +279,16 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
     while ((1 << bits) < g.rows - kMaxK + 1) ++bits;
     p.row_bits = bits < 1 ? 1 : bits;
     p.ok = (int64_t)p.n_chunks * slab <= (4ll << 30) ? 1 : 0;
+    p.shared = 0;
+    p.n_slabs = p.n_chunks;
+    // Tables too large for one partial slab per chunk: a single slab, the chunks walked one launch after
+    // the other, each adding its sums to the rows it touches (the launches are ordered by the stream, so
+    // the summation order is still fixed).
+    if (!p.ok && allow_shared && slab <= (8ll << 30)) {
+        p.ok = 1;
+        p.shared = 1;
+        p.n_slabs = 1;
+    }
     return p;
 }
 
@@ -285,7 +296,7 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B)
 #define KAN_WALK_VARIANT(name)                                                                                      \
     void name(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const WalkRecords &rec, const float *gy, \
               const float *cf, const float *w_b, float *part_c, float *part_b, float *gx, int64_t B,              \
-              const WalkPlan &p, int bpc, int m, int prezeroed, float *carry)
+              const WalkPlan &p, int bpc, int m, int prezeroed, float *carry, int chunk0, int n_chunks)
 KAN_WALK_VARIANT(walk_launch_s1t8);
 KAN_WALK_VARIANT(walk_launch_s1t4);
 KAN_WALK_VARIANT(walk_launch_s2t4);
@@ -354,40 +365,47 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     float *carry = (float *)at;
     if (hipError_t e = launch_sorted_records(g, x, xT, B, p.S, p.row_bits, rec, st); e != hipSuccess) return e;
     const int bpc = (p.n_seg * p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
-    int m = 1;
-    while (m * 2 <= 8 && m * 2 <= p.n_chunks) m *= 2;
-    const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
-    const unsigned blocks = (unsigned)(8 * bpc_sub * ((p.n_chunks + m - 1) / m));
     float *gx_out = dx ? (p.n_jt > 1 ? gx_part : gx) : nullptr;
     // Sparse regime (far more rows than a chunk has samples): most rows of a chunk's partial slab
     // receive nothing.  The slab is zeroed with a streaming fill and the walk skips the gaps instead of
-    // stepping through them row by row.
-    const int prezeroed = (part_c != nullptr && g.rows > 2 * p.S) ? 1 : 0;
+    // stepping through them row by row.  A shared slab is always used this way.
+    const int prezeroed = (part_c != nullptr && (g.rows > 2 * p.S || p.shared)) ? 1 : 0;
     if (prezeroed) {
-        const int64_t n4 = (int64_t)p.n_chunks * g.n_in * g.rows * g.n_out;
+        const int64_t n4 = (int64_t)p.n_slabs * g.n_in * g.rows * g.n_out;
         prof::Timed tm("walk_zero_fill", st);
         fill_zero_kernel<<<(unsigned)((n4 + 1023) / 1024), 256, 0, st>>>(part_c, n4);
     }
-    {
-        prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
-        if (p.T == 8 && p.streams == 1)
-            walk_launch_s1t8(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
-        else if (p.T == 4 && p.streams == 1)
-            walk_launch_s1t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
-        else if (p.T == 4 && p.streams == 2)
-            walk_launch_s2t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
-        else if (p.T == 4 && p.streams == 4)
-            walk_launch_s4t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
-        else if (p.T == 1 && p.streams == 4)
-            walk_launch_s4t1(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry);
-        else
-            return hipErrorInvalidValue;
-    }
-    if (part_c != nullptr && p.n_seg > 1) {
-        const int64_t nn = (int64_t)p.n_chunks * g.n_in * g.n_out;
-        prof::Timed tm("walk_carry", st);
-        walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.S, p.n_chunks,
-                                                                       p.n_seg);
+    // one launch for all chunks, or (shared slab) one launch per chunk, each followed by its carry rows
+    const int launches = p.shared ? p.n_chunks : 1;
+    const int per_launch = p.shared ? 1 : p.n_chunks;
+    int m = 1;
+    while (m * 2 <= 8 && m * 2 <= per_launch) m *= 2;
+    const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
+    const unsigned blocks = (unsigned)(8 * bpc_sub * ((per_launch + m - 1) / m));
+    for (int l = 0; l < launches; ++l) {
+        const int chunk0 = p.shared ? l : 0;
+        {
+            prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
+            if (p.T == 8 && p.streams == 1)
+                walk_launch_s1t8(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+            else if (p.T == 4 && p.streams == 1)
+                walk_launch_s1t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+            else if (p.T == 4 && p.streams == 2)
+                walk_launch_s2t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+            else if (p.T == 4 && p.streams == 4)
+                walk_launch_s4t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+            else if (p.T == 1 && p.streams == 4)
+                walk_launch_s4t1(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+            else
+                return hipErrorInvalidValue;
+        }
+        if (part_c != nullptr && p.n_seg > 1) {
+            const int64_t nn = (int64_t)per_launch * g.n_in * g.n_out;
+            prof::Timed tm("walk_carry", st);
+            walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.S, per_launch,
+                                                                           p.n_seg, chunk0, p.shared);
+        }
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }
     if (dx && p.n_jt > 1) {
         const int64_t nn = B * g.n_in;

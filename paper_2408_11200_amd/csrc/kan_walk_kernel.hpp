@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                                                             float *__restrict__ part_c, float *__restrict__ part_b,
                                                             float *__restrict__ gx, int64_t B, int S, int n_chunks,
                                                             int n_jt, int blocks_per_chunk, int xcd_groups, int prezeroed, int n_seg,
-                                                            float *__restrict__ carry)
+                                                            float *__restrict__ carry, int chunk0, int shared)
 {
     constexpr int LPS = 64 / STREAMS;
     constexpr int RPW = LPS / 4;                    // records whose weights fit one register of a stream
@@ -148,10 +148,13 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     const int grp = xcd % xcd_groups, n_sub = 8 / xcd_groups, sub_x = xcd / xcd_groups;
     const int bpc_sub = (blocks_per_chunk + n_sub - 1) / n_sub;
-    const int c = grp + xcd_groups * (slot / bpc_sub);
+    // n_chunks counts the chunks of this launch, the first of which is chunk0 of the batch.  shared: all
+    // chunks use the one partial slab, launch after launch, adding to what it holds.
+    const int c_local = grp + xcd_groups * (slot / bpc_sub);
+    const int c = chunk0 + c_local;
     const int blk = (slot % bpc_sub) * n_sub + sub_x;
     const int ws = (blk * 4 + wave) * STREAMS + sub;
-    if (c >= n_chunks || blk >= blocks_per_chunk || ws >= n_seg * n_jt * g.n_in) return;
+    if (c_local >= n_chunks || blk >= blocks_per_chunk || ws >= n_seg * n_jt * g.n_in) return;
     const int i = ws % g.n_in;
     const int jt = (ws / g.n_in) % n_jt;
     const int seg = ws / (g.n_in * n_jt);
@@ -165,10 +168,10 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     const int64_t list = list0 + (int64_t)seg * seg_len;        // this segment's records
     // The segment owns the table rows from its first record's row up to the next segment's first
     // row; what its window holds beyond that at the end goes to the next segment's carry rows.
-    const int r_next = seg + 1 < n_seg ? (rec.rt[list + seg_len] & 0xffff) : g.rows;
+    const int r_next = seg + 1 < n_seg ? (rec.rt[list + seg_len] & kRtRowMask) : g.rows;
     const float *gyp = gy + b0 * g.n_out + jc;
     const bool store_c = jok && part_c != nullptr;
-    float *out = part_c + ((int64_t)c * g.n_in + i) * g.rows * g.n_out + jc;
+    float *out = part_c + ((int64_t)(shared ? 0 : c) * g.n_in + i) * g.rows * g.n_out + jc;
     const float *cfi = DX ? cf + (int64_t)i * g.slab_rows * g.n_out + jc : nullptr;
     float *gxo = DX ? gx + (int64_t)jt * B * g.n_in + b0 * g.n_in + i : nullptr;
 
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         hi[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
 
-    int cur = rec.rt[list] & 0xffff;         // first row of the window the accumulators stand on
+    int cur = rec.rt[list] & kRtRowMask;     // first row of the window the accumulators stand on
     if (store_c && !prezeroed && seg == 0)
         for (int m = 0; m < cur; ++m) store_vec<T>(out + (int64_t)m * g.n_out, zero);
 
@@ -218,7 +221,18 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                 hi[r][SL] = 0.0f;
             }
         }
-        if (store && store_c) store_vec<T>(out + (int64_t)cur * g.n_out, gone);
+        if (store && store_c) {
+            float *dst = out + (int64_t)cur * g.n_out;
+            if (shared) {               // uniform: add to what earlier chunks left in the row
+                float old[T];
+                load_vec<T>(dst, old);
+#pragma unroll
+                for (int r = 0; r < T; ++r) old[r] += gone[r];
+                store_vec<T>(dst, old);
+            } else {
+                store_vec<T>(dst, gone);
+            }
+        }
         if (DX && enter_next) {
             const int enter = cur + kMaxK < g.rows ? cur + kMaxK : g.rows - 1;     // clamped: unused past the end
             load_vec<T>(cfi + (int64_t)enter * g.n_out, cw[SL]);
@@ -288,10 +302,10 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
             load_vec<T>(gyp + (int64_t)t * g.n_out, dst[N]);
         });
     };
-    gather((int)((unsigned)mine.rt >> 16), std::integral_constant<int, 0>{}, gbuf[0]);
+    gather((int)((unsigned)mine.rt >> kRtRowBits), std::integral_constant<int, 0>{}, gbuf[0]);
     for (int bi = 0; bi < nb; ++bi) {
         const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
-        const int rowv = mine.rt & 0xffff, tv = (int)((unsigned)mine.rt >> 16);
+        const int rowv = mine.rt & kRtRowMask, tv = (int)((unsigned)mine.rt >> kRtRowBits);
         float dot[16];
         bool quad_same = false;
         // The 16 records go in groups of four.  The gy rows of the next group (the first of the next
@@ -301,7 +315,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
             constexpr int H = decltype(h)::value;
             auto &gr = gbuf[H & 1];
             if constexpr (H + 1 < 16 / GROUP) gather(tv, std::integral_constant<int, H + 1>{}, gbuf[(H + 1) & 1]);
-            else gather((int)((unsigned)upcoming.rt >> 16), std::integral_constant<int, 0>{}, gbuf[0]);
+            else gather((int)((unsigned)upcoming.rt >> kRtRowBits), std::integral_constant<int, 0>{}, gbuf[0]);
             static_for<0, GROUP>([&](auto n) {
                 constexpr int N = decltype(n)::value;
                 constexpr int R = H * GROUP + N;
@@ -420,12 +434,13 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
 template <int STREAMS, int T>
 void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, const WalkRecords &rec,
                         const float *gy, const float *cf, const float *w_b, float *part_c, float *part_b, float *gx,
-                        int64_t B, const WalkPlan &p, int bpc, int m, int prezeroed, float *carry)
+                        int64_t B, const WalkPlan &p, int bpc, int m, int prezeroed, float *carry, int chunk0,
+                        int n_chunks)
 {
     auto kern = dx ? (p.S > 1024 ? backward_walk_kernel<STREAMS, T, true, true> : backward_walk_kernel<STREAMS, T, true, false>)
                    : (p.S > 1024 ? backward_walk_kernel<STREAMS, T, false, true> : backward_walk_kernel<STREAMS, T, false, false>);
-    kern<<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S, p.n_chunks, p.n_jt, bpc, m, prezeroed,
-                                 p.n_seg, carry);
+    kern<<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S, n_chunks, p.n_jt, bpc, m, prezeroed,
+                                 p.n_seg, carry, chunk0, p.shared);
 }
 
 }  // namespace

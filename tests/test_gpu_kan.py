@@ -30,7 +30,11 @@ def assert_close(got, ref, tol, what):
     return float((err / bound).max())
 
 
-def run_layer_parity(w, rows=None, check_grads=True):
+def run_layer_parity(w, rows=None, check_grads=True, gx_in_grid_units=False):
+    """gx_in_grid_units: compare h * dL/dx (the gradient with respect to the position in cell widths)
+    instead of dL/dx.  dL/dx = (1/h) dL/du: on a grid with 1/h in the tens of thousands it is a sum of
+    terms that large, whose fp32 rounding error is relative to them, while the tolerance's absolute part
+    is meant for O(1) results; in grid units the terms are O(1) again."""
     s, p = w.layers[0], w.params[0]
     inv_h = oracle.inv_h_of(s.grid_lo, s.grid_hi, s.G)
     x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
@@ -48,7 +52,8 @@ def run_layer_parity(w, rows=None, check_grads=True):
             ref = oracle.kan_backward(w.x, p["coef"], p["w_s"], p["w_b"], w.gy, s.G, s.k, s.grid_lo, inv_h,
                                       s.base_act)
             for name in ("gx", "gcoef", "gw_s", "gw_b"):
-                assert_close(g[name], ref[name], GRAD_TOL, name)
+                unit = 1.0 / float(inv_h) if (name == "gx" and gx_in_grid_units) else 1.0
+                assert_close(g[name].double() * unit, ref[name] * unit, GRAD_TOL, name)
         else:
             ref = oracle.kan_backward(w.x[sel], p["coef"], p["w_s"], p["w_b"], w.gy[sel], s.G, s.k, s.grid_lo,
                                       inv_h, s.base_act, want=("gx",))
@@ -73,7 +78,8 @@ SWEEP = [
     (300, 9, 12, 30, 3, 0.1),          # narrow layer, one output per lane
     (700, 5, 32, 3000, 3, 0.1),        # far more rows than samples: pre-zeroed partial slabs, gap jumps
     (1500, 3, 256, 2500, 2, 0.05),     # the same with one stream per wave
-    (64, 2, 8, 70000, 3, 0.1),         # more rows than the sorted path indexes: generic kernels
+    (64, 2, 8, 70000, 3, 0.1),         # 17-bit row numbers in the sorted records (three sort digits)
+    (64, 2, 8, 600000, 3, 0.1),        # more rows than the sorted path indexes (2^19): generic kernels
 ]
 
 
@@ -308,6 +314,34 @@ def test_config4_large_grid_full_size():
 def test_paper_shape_full_size(G):
     """32->32, k=3, N=2^17 (the shape of the paper's throughput table), smallest and largest grid."""
     run_layer_parity(workloads.paper_shape(G))
+
+
+@pytest.mark.parametrize("G", [1 << 16, 1 << 18])
+def test_paper_shape_huge_grids(G):
+    """The same shape with 2^16 and 2^18 cells (tables of 0.27 and 1.07 GB): per-chunk partial tables no
+    longer fit, so the 16 chunks of the batch take turns adding to one shared partial table."""
+    run_layer_parity(workloads.paper_shape(G), gx_in_grid_units=True)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 5])
+def test_paper_shape_degrees(k):
+    """32->32, G=64, N=2^16 at the other degrees of the degree sweep (k = 3 is covered above)."""
+    run_layer_parity(workloads.paper_shape(64, B=1 << 16, k=k))
+
+
+@pytest.mark.parametrize("B,n_in,n_out,G", [(460000, 4, 16, 300000), (458753, 12, 6, 300000)])
+def test_shared_partial_table(B, n_in, n_out, G):
+    """Long batch x long table: 57 chunks of 8192 samples whose partial tables together would exceed the
+    budget, so they share one (four outputs per lane, then one output per lane); ragged last chunk."""
+    w = workloads.random_kan_layer(9100 + n_out, B, n_in, n_out, G, 3, outside_frac=0.02)
+    run_layer_parity(w, gx_in_grid_units=True)
+    # and bit for bit the same on a second run: the chunks add to the shared table in stream order
+    s, p = w.layers[0], w.params[0]
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    a = binding.kan_backward(s, x, coef, w_s, w_b, gy)
+    b = binding.kan_backward(s, x, coef, w_s, w_b, gy)
+    for n in a:
+        assert torch.equal(a[n], b[n]), n
 
 
 def test_dense_gemm_baseline_matches_oracle():

@@ -264,6 +264,7 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "p"],
                     help="c1..c5: the benchmark configurations; p: the paper's 32->32, N=2^17 shape (see --grid)")
     ap.add_argument("--grid", type=int, default=64, help="grid size G of workload p")
+    ap.add_argument("--batch", type=int, default=1 << 17, help="batch size of workload p")
     ap.add_argument("--degree", type=int, default=3, help="spline degree k of workload p (1..5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=10,
@@ -292,7 +293,7 @@ def main():
         case = KanStackCase(workloads.config1(), torch, binding)
     else:
         w = {"c2": workloads.config2, "c3": workloads.config3, "c4": workloads.config4,
-             "p": lambda: workloads.paper_shape(args.grid, k=args.degree)}[args.workload]()
+             "p": lambda: workloads.paper_shape(args.grid, B=args.batch, k=args.degree)}[args.workload]()
         case = KanCase(w, torch, binding)
 
     if args.copy_calibration:
@@ -374,6 +375,14 @@ def main():
     dense = None
     if args.dense_baseline and isinstance(case, KanCase):
         s = case.s
+        need = [binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_FORWARD),
+                binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_BACKWARD)]
+        free_bytes = torch.cuda.mem_get_info()[0]
+        if s.k > 3 or max(need) > 0.8 * free_bytes:
+            # the baseline materialises all G + k basis values of every (sample, input) pair
+            dense = {"workspace_bytes_dense": need, "free_device_bytes": free_bytes,
+                     "note": "not run: " + ("degrees 1..3 only" if s.k > 3 else "its workspace does not fit the device")}
+    if args.dense_baseline and isinstance(case, KanCase) and dense is None:
         ws_d = torch.empty(binding.kan_dense_baseline_workspace_bytes(s, case.w.B, binding.PASS_FORWARD),
                            dtype=torch.uint8, device="cuda")
         for _ in range(2):

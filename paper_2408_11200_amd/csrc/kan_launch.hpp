@@ -107,11 +107,11 @@ struct WalkPlan {
     int streams, T;      // streams per wave, outputs per lane
     int n_jt;            // output tiles of (64 / streams) * T outputs
     int row_bits;        // bits of the largest window row (sort key width)
-    int shared;          // 1: one partial slab for all chunks, which are walked one after the other
-    int n_slabs;         // partial slabs the walk writes: n_chunks, or 1 when shared
+    int shared;          // 1: fewer partial slabs than chunks; the chunks are walked in rounds of n_slabs
+    int n_slabs;         // partial slabs the walk writes: n_chunks, or what fits the budget when shared
 };
 // allow_shared: tables whose per-chunk partial slabs would not fit the budget are still planned, with the
-// chunks taking turns on a single slab (ok stays 0 for them otherwise).
+// chunks taking turns on the slabs that fit (ok stays 0 for them otherwise).
 WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared = false);
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out);
 hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,

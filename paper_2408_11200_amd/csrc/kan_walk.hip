@@ -194,13 +194,13 @@ __global__ __launch_bounds__(256) void walk_carry_kernel(SplineGeom g, const int
                                                          const float *__restrict__ carry, float *__restrict__ part_c,
                                                          int S, int n_chunks, int n_seg, int chunk0, int shared)
 {
-    // n_chunks chunks starting at chunk0 of the batch; shared: they all add to the one slab
+    // n_chunks chunks starting at chunk0 of the batch; shared: the launch's chunk number l adds to slab l
     const int64_t at = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (at >= (int64_t)n_chunks * g.n_in * g.n_out) return;
     const int j = (int)(at % g.n_out);
     const int64_t ci = (int64_t)chunk0 * g.n_in + at / g.n_out;               // chunk * n_in + input
     const int seg_len = S / n_seg;
-    float *slab = part_c + (shared ? ci % g.n_in : ci) * g.rows * g.n_out + j;
+    float *slab = part_c + (shared ? at / g.n_out : ci) * g.rows * g.n_out + j;
     for (int k = 1; k < n_seg; ++k) {
         const int rf = rt[ci * S + (int64_t)k * seg_len] & kRtRowMask;
         const float *cr = carry + ((ci * n_seg + k) * kMaxK) * g.n_out + j;
@@ -271,23 +271,29 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared)
     p.sbits = log2_exact(S);
     p.n_chunks = (int)((B + S - 1) / S);
     // segments per list: enough for about 2048 waves, at least 64 records each
-    p.n_seg = 1;
-    while (S / (p.n_seg * 2) >= 64 &&
-           (int64_t)p.n_chunks * p.n_seg * p.n_jt * g.n_in < (int64_t)2048 * p.streams)
-        p.n_seg *= 2;
     int bits = 0;
     while ((1 << bits) < g.rows - kMaxK + 1) ++bits;
     p.row_bits = bits < 1 ? 1 : bits;
     p.ok = (int64_t)p.n_chunks * slab <= (4ll << 30) ? 1 : 0;
     p.shared = 0;
     p.n_slabs = p.n_chunks;
-    // Tables too large for one partial slab per chunk: a single slab, the chunks walked one launch after
-    // the other, each adding its sums to the rows it touches (the launches are ordered by the stream, so
-    // the summation order is still fixed).
+    auto plan_segments = [&](int chunks_per_launch) {
+        p.n_seg = 1;
+        while (S / (p.n_seg * 2) >= 64 &&
+               (int64_t)chunks_per_launch * p.n_seg * p.n_jt * g.n_in < (int64_t)2048 * p.streams)
+            p.n_seg *= 2;
+    };
+    plan_segments(p.n_chunks);
+    // Tables too large for one partial slab per chunk: as many slabs as fit the budget (at least one),
+    // the chunks walked in rounds of that many, one launch per round, chunk number l of a round adding its
+    // sums to the rows it touches in slab l (the launches are ordered by the stream and every row of a slab
+    // has one writer per launch, so the summation order is still fixed).
     if (!p.ok && allow_shared && slab <= (8ll << 30)) {
         p.ok = 1;
         p.shared = 1;
-        p.n_slabs = 1;
+        const int64_t fit = (4ll << 30) / slab;
+        p.n_slabs = (int)(fit < 1 ? 1 : (fit > p.n_chunks ? p.n_chunks : fit));
+        plan_segments(p.n_slabs);
     }
     return p;
 }
@@ -375,34 +381,36 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
         prof::Timed tm("walk_zero_fill", st);
         fill_zero_kernel<<<(unsigned)((n4 + 1023) / 1024), 256, 0, st>>>(part_c, n4);
     }
-    // one launch for all chunks, or (shared slab) one launch per chunk, each followed by its carry rows
-    const int launches = p.shared ? p.n_chunks : 1;
-    const int per_launch = p.shared ? 1 : p.n_chunks;
+    // one launch for all chunks, or (shared slabs) one launch per round of n_slabs chunks, each followed by
+    // its carry rows
+    const int per_launch = p.shared ? p.n_slabs : p.n_chunks;
+    const int launches = (p.n_chunks + per_launch - 1) / per_launch;
     int m = 1;
     while (m * 2 <= 8 && m * 2 <= per_launch) m *= 2;
     const int bpc_sub = (bpc + 8 / m - 1) / (8 / m);
     const unsigned blocks = (unsigned)(8 * bpc_sub * ((per_launch + m - 1) / m));
     for (int l = 0; l < launches; ++l) {
-        const int chunk0 = p.shared ? l : 0;
+        const int chunk0 = l * per_launch;
+        const int here = p.n_chunks - chunk0 < per_launch ? p.n_chunks - chunk0 : per_launch;
         {
             prof::Timed tm(dx ? "backward_walk" : "dparam_walk", st);
             if (p.T == 8 && p.streams == 1)
-                walk_launch_s1t8(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+                walk_launch_s1t8(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else if (p.T == 4 && p.streams == 1)
-                walk_launch_s1t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+                walk_launch_s1t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else if (p.T == 4 && p.streams == 2)
-                walk_launch_s2t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+                walk_launch_s2t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else if (p.T == 4 && p.streams == 4)
-                walk_launch_s4t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+                walk_launch_s4t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else if (p.T == 1 && p.streams == 4)
-                walk_launch_s4t1(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, per_launch);
+                walk_launch_s4t1(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else
                 return hipErrorInvalidValue;
         }
         if (part_c != nullptr && p.n_seg > 1) {
-            const int64_t nn = (int64_t)per_launch * g.n_in * g.n_out;
+            const int64_t nn = (int64_t)here * g.n_in * g.n_out;
             prof::Timed tm("walk_carry", st);
-            walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.S, per_launch,
+            walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.S, here,
                                                                            p.n_seg, chunk0, p.shared);
         }
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;

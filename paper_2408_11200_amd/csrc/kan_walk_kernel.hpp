@@ -148,8 +148,8 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     const int grp = xcd % xcd_groups, n_sub = 8 / xcd_groups, sub_x = xcd / xcd_groups;
     const int bpc_sub = (blocks_per_chunk + n_sub - 1) / n_sub;
-    // n_chunks counts the chunks of this launch, the first of which is chunk0 of the batch.  shared: all
-    // chunks use the one partial slab, launch after launch, adding to what it holds.
+    // n_chunks counts the chunks of this launch, the first of which is chunk0 of the batch; the launch's
+    // chunk number l uses partial slab l.  shared: a slab holds the sums of earlier launches, add to them.
     const int c_local = grp + xcd_groups * (slot / bpc_sub);
     const int c = chunk0 + c_local;
     const int blk = (slot % bpc_sub) * n_sub + sub_x;
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     const int r_next = seg + 1 < n_seg ? (rec.rt[list + seg_len] & kRtRowMask) : g.rows;
     const float *gyp = gy + b0 * g.n_out + jc;
     const bool store_c = jok && part_c != nullptr;
-    float *out = part_c + ((int64_t)(shared ? 0 : c) * g.n_in + i) * g.rows * g.n_out + jc;
+    float *out = part_c + ((int64_t)c_local * g.n_in + i) * g.rows * g.n_out + jc;
     const float *cfi = DX ? cf + (int64_t)i * g.slab_rows * g.n_out + jc : nullptr;
     float *gxo = DX ? gx + (int64_t)jt * B * g.n_in + b0 * g.n_in + i : nullptr;
 
@@ -223,12 +223,12 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         }
         if (store && store_c) {
             float *dst = out + (int64_t)cur * g.n_out;
-            if (shared) {               // uniform: add to what earlier chunks left in the row
-                float old[T];
-                load_vec<T>(dst, old);
+            if (shared) {
+                // uniform.  Add to what earlier chunks left in the row.  Within a launch this wave is the
+                // only writer of the row and launches follow each other on the stream, so the sum is the
+                // same every run; the hardware add is used because it does not wait for the old value.
 #pragma unroll
-                for (int r = 0; r < T; ++r) old[r] += gone[r];
-                store_vec<T>(dst, old);
+                for (int r = 0; r < T; ++r) unsafeAtomicAdd(dst + r, gone[r]);
             } else {
                 store_vec<T>(dst, gone);
             }
@@ -439,8 +439,9 @@ void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, 
 {
     auto kern = dx ? (p.S > 1024 ? backward_walk_kernel<STREAMS, T, true, true> : backward_walk_kernel<STREAMS, T, true, false>)
                    : (p.S > 1024 ? backward_walk_kernel<STREAMS, T, false, true> : backward_walk_kernel<STREAMS, T, false, false>);
+    // the first round of a shared run finds its slabs zero and stores like an unshared run
     kern<<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S, n_chunks, p.n_jt, bpc, m, prezeroed,
-                                 p.n_seg, carry, chunk0, p.shared);
+                                 p.n_seg, carry, chunk0, (p.shared && chunk0 > 0) ? 1 : 0);
 }
 
 }  // namespace

@@ -60,7 +60,7 @@ def measured_traffic(workload, family):
 # gradients in one kernel: two thirds)
 KERNEL_ROLE = {
     "forward_generic": "forward", "dx_generic": "dx", "dparam_generic": "dparam",
-    "forward_lds": "forward", "forward_pairs": "forward", "forward_rows": "forward", "dparam_walk": "dparam", "backward_walk": "backward",
+    "forward_lds": "forward", "forward_pairs": "forward", "forward_lds_rows": "forward", "forward_rows": "forward", "dparam_walk": "dparam", "backward_walk": "backward",
     "forward_narrow": "forward", "dx_narrow": "dx",
 }
 ROLE_SHARE = {"forward": 1, "dx": 1, "dparam": 1, "backward": 2}

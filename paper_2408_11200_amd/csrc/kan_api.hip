@@ -159,6 +159,7 @@ static int forward_impl(const kan_layer_desc *desc, int64_t B, const float *x, c
     hipError_t e = narrow_applicable(g)    ? launch_forward_narrow(g, x, cf, w_b, y, B, st)
                    : forward_rows_plan(g) ? launch_forward_rows(g, x, cf, y, B, st)
                    : forward_lds_plan(g)  ? launch_forward_lds(g, x, cf, y, B, st)
+                   : forward_lds_rows_plan(g, B) ? launch_forward_lds_rows(g, x, cf, y, B, st)
                                          : launch_forward_generic(g, x, cf, w_b, y, B, st);
     return e == hipSuccess ? KAN_OK : KAN_ERR_HIP;
 }

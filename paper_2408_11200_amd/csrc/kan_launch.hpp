@@ -80,6 +80,12 @@ int forward_lds_plan(const SplineGeom &g);
 hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
                               hipStream_t st);
 
+// LDS-staged kernel for long tables (narrow output tile, many samples per workgroup); the plan
+// returns 0 when the shape does not qualify
+int forward_lds_rows_plan(const SplineGeom &g, int64_t B);
+hipError_t launch_forward_lds_rows(const SplineGeom &g, const float *x, const float *cf, float *y, int64_t B,
+                                   hipStream_t st);
+
 // Sorted pair records of the walk, one per (sample, input) pair, as a structure of arrays indexed
 // [chunk][input][rank in the chunk's sorted order]: first row of the K-wide window (clamped into the
 // table; kRtRowBits bits) | the sample's index inside its chunk << kRtRowBits (chunks hold at most

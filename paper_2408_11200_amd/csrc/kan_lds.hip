@@ -27,23 +27,9 @@ struct WinPair {
 template <bool GRAD>
 __device__ __forceinline__ WinPair window_pair(float x, const SplineGeom &g, int i)
 {
-    Pair p = pair_eval<GRAD>(x, g, i);
+    const Pair p = pair_eval<GRAD>(x, g, i);
     WinPair o;
-    const int hi = g.rows - kMaxK;
-    const int cc = p.cell < 0 ? 0 : (p.cell > hi ? hi : p.cell);
-    const int d = cc - p.cell;                 // row cc + s holds weight index s + d
-#pragma unroll
-    for (int s = 0; s < kMaxK; ++s) {
-        float v = 0.0f;
-#pragma unroll
-        for (int q = 0; q < kMaxK; ++q) {
-            const float src = GRAD ? p.dw[q] : p.w[q];
-            v = (s + d == q) ? src : v;
-        }
-        o.w[s] = v;
-    }
-    o.row0 = cc;
-    o.base = GRAD ? p.dbase : p.base;
+    window_of<GRAD>(p, g.rows, o.row0, o.w, o.base);
     return o;
 }
 

@@ -238,8 +238,9 @@ int forward_impl(const ukan_layer_desc *desc, int64_t B, const float *x, const u
     rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr, saved);
     if (rc != KAN_OK) return rc;
     if (span) *span = pr.n_g;
-    hipError_t e = narrow_applicable(pr.g) ? launch_forward_narrow(pr.g, x, pr.cf, p->w_b, y, B, st)
-                                           : launch_forward_generic(pr.g, x, pr.cf, p->w_b, y, B, st);
+    hipError_t e = narrow_applicable(pr.g)            ? launch_forward_narrow(pr.g, x, pr.cf, p->w_b, y, B, st)
+                   : forward_lds_rows_plan(pr.g, B) ? launch_forward_lds_rows(pr.g, x, pr.cf, y, B, st)
+                                                    : launch_forward_generic(pr.g, x, pr.cf, p->w_b, y, B, st);
     if (e != hipSuccess) return KAN_ERR_HIP;
     return KAN_OK;
 }

@@ -271,6 +271,10 @@ def main():
                     help="steps of the separate pass that times every kernel with events (0: skip it)")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="also time the dense basis x coefficient GEMM formulation of the forward pass")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays (bounded-grid workloads; the UKAN calls synchronise)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="run the instruction-rate microbenchmarks of the benchmark library instead of a workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -286,6 +290,14 @@ def main():
         print("no GPU visible", file=sys.stderr)
         return 2
     binding.load()
+
+    if args.ceilings:
+        # one JSON line per microbenchmark and workgroup size; rates per CU and for the 256 CUs of the chip
+        for threads in (256, 512, 1024):
+            for name, unit, rate, ms in binding.kan_bench_ceilings(threads, 20000 if threads > 256 else 40000):
+                print(json.dumps({"ceiling": name, "threads_per_cu": threads, "unit": unit, "per_cu_per_s": rate,
+                                  "chip_per_s": 256 * rate, "kernel_ms": ms}))
+        return 0
 
     if args.workload == "c5":
         case = UkanCase(workloads.config5(), torch, binding)
@@ -309,9 +321,23 @@ def main():
     for _ in range(args.warmup):
         case.step()
     torch.cuda.synchronize()
+    run_step = case.step
+    if args.graph:
+        if isinstance(case, UkanCase):
+            print("--graph: the UKAN entry points synchronise the stream and cannot be captured", file=sys.stderr)
+            return 2
+        # the kan_* calls only enqueue kernels on the current stream (no allocation, no memset, no
+        # synchronisation), so one step can be captured as it is and replayed
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            case.step()
+        run_step = graph.replay
+        for _ in range(args.warmup):
+            run_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        case.step()
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -430,6 +456,8 @@ def main():
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
             "data": "synthetic", "config": case.config, "roofline": rl, "cpu_baseline": cpu, "passes": passes}
+    if args.graph:
+        line["config"] = dict(case.config, launch="one HIP graph replay per step")
     if dense:
         line["dense_baseline"] = dense
     print(json.dumps(line))

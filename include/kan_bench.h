@@ -50,6 +50,16 @@ int kan_dense_baseline_backward(const kan_layer_desc *desc, int64_t B, const flo
                                 const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
                                 float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream);
 
+/* Instruction-rate ceilings of a compute unit (fp32 multiply-add, LDS reads / writes / atomic adds, the
+   4x4x1 fp32 matrix-core instruction), the yardsticks the layer kernels' counters are read against.
+   kan_bench_ceiling runs microbenchmark number `index` (0 .. kan_bench_ceiling_count() - 1) with one
+   workgroup of threads_per_cu (256, 512 or 1024) threads on each of 256 CUs for `iters` iterations on the
+   default stream, synchronises, and returns its name, the unit it counts ("FMA" or "B" for LDS bytes),
+   units per CU per second and the kernel time.  Allocates and frees a small device buffer. */
+int kan_bench_ceiling_count(void);
+int kan_bench_ceiling(int index, int threads_per_cu, int iters, const char **name, const char **unit,
+                      double *per_cu_per_second, double *ms);
+
 #ifdef __cplusplus
 }
 #endif

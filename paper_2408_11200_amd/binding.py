@@ -31,7 +31,8 @@ EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward",
 
 BENCH_EXPORTS = ["kan_profile_before", "kan_profile_after", "kan_profile_enable", "kan_profile_read",
                  "kan_dense_baseline_workspace_bytes", "kan_dense_baseline_forward",
-                 "kan_dense_baseline_backward_workspace_bytes", "kan_dense_baseline_backward"]
+                 "kan_dense_baseline_backward_workspace_bytes", "kan_dense_baseline_backward",
+                 "kan_bench_ceiling_count", "kan_bench_ceiling"]
 
 
 class KanLayerDesc(ctypes.Structure):
@@ -143,6 +144,12 @@ def load_bench():
                                                 vp, sz, vp]
     lib.kan_dense_baseline_forward.restype = ctypes.c_int
     lib.kan_dense_baseline_forward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kan_bench_ceiling_count.restype = ctypes.c_int
+    lib.kan_bench_ceiling_count.argtypes = []
+    lib.kan_bench_ceiling.restype = ctypes.c_int
+    lib.kan_bench_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                      ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]
     _bench = lib
     return lib
 
@@ -307,6 +314,20 @@ def kan_set_launch_observer(before, after):
     rc = load().kan_set_launch_observer(as_vp(before), as_vp(after))
     if rc != KAN_OK:
         raise KanError(rc, "kan_set_launch_observer")
+
+
+def kan_bench_ceilings(threads_per_cu=1024, iters=20000):
+    """[(name, unit, units per CU per second, kernel ms)] of the benchmark library's instruction-rate microbenchmarks."""
+    lib = load_bench()
+    rows = []
+    for q in range(lib.kan_bench_ceiling_count()):
+        name, unit, rate, ms = ctypes.c_char_p(), ctypes.c_char_p(), ctypes.c_double(), ctypes.c_double()
+        rc = lib.kan_bench_ceiling(q, threads_per_cu, iters, ctypes.byref(name), ctypes.byref(unit), ctypes.byref(rate),
+                                   ctypes.byref(ms))
+        if rc != KAN_OK:
+            raise KanError(rc, "kan_bench_ceiling")
+        rows.append((name.value.decode(), unit.value.decode(), rate.value, ms.value))
+    return rows
 
 
 def kan_profile_enable(on):

@@ -288,6 +288,54 @@ def test_config1_two_layer_chain_with_mse():
         assert_close(g1[name], r1[name], GRAD_TOL, "layer1 " + name)
 
 
+def test_step_captured_in_a_graph_replays_to_the_eager_result():
+    """Forward + backward of the two config-1 layers and of a walk-path layer captured in one HIP graph (the
+    calls only enqueue kernels: no allocation, no memset node, no synchronisation).  Every replay must give
+    the eager result bit for bit, with eager work and synchronisations between the replays and with the
+    inputs changed in place before the last one."""
+    w = workloads.random_kan_layer(31, 3000, 24, 128, 12, 3, outside_frac=0.1)
+    s, p = w.layers[0], w.params[0]
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    y = torch.empty((w.B, s.n_out), device="cuda")
+    out = {"gx": torch.empty_like(x), "gcoef": torch.empty_like(coef), "gw_s": torch.empty_like(w_s),
+           "gw_b": torch.empty_like(w_b)}
+    ws_f = torch.empty(binding.kan_workspace_bytes(s, w.B, binding.PASS_FORWARD), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.kan_workspace_bytes(s, w.B, binding.PASS_BACKWARD), dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.kan_forward(s, x, coef, w_s, w_b, y=y, ws=ws_f)
+        binding.kan_backward(s, x, coef, w_s, w_b, gy, out=out, ws=ws_b)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [y.clone()] + [out[n].clone() for n in sorted(out)]
+
+    step()                              # eager warm-up (sets the kernels' LDS limits) and reference
+    ref = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        y.zero_()
+        for t in out.values():
+            t.fill_(7.0)
+        ws_b.fill_(0x5A)                # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, ref):
+            assert torch.equal(a, b)
+        binding.kan_forward(s, x, coef, w_s, w_b)       # unrelated eager work between replays
+    x.mul_(0.5)
+    gy.neg_()
+    step()
+    ref2 = snapshot()
+    graph.replay()
+    for a, b in zip(snapshot(), ref2):
+        assert torch.equal(a, b)
+    assert not torch.equal(ref2[0], ref[0])
+
+
 def test_config2_full_size():
     """64->64, G=10, batch 65536 with 5% of the samples outside the grid: every output element."""
     run_layer_parity(workloads.config2())

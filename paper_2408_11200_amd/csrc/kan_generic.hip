@@ -1,6 +1,7 @@
 // Generic kernels of the local B-spline layer: they work for every shape the
-// library accepts (any n_in, n_out, grid size, k <= 3, per-input cell offsets)
-// and are the fallback when no specialised kernel applies.
+// library accepts (any n_in, n_out, grid size, per-input cell offsets; degrees up to
+// kMaxK - 1: 3 in the default build, 5 in the build of kan_generic_k5.hip) and are the
+// fallback when no specialised kernel applies.
 //
 // Common mapping: lanes <-> outputs.  One wave owns T samples and a tile of
 // 64*R outputs; the per-(sample, input) quantities (cell, window weights, base

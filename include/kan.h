@@ -58,8 +58,7 @@ enum { KAN_BASE_NONE = 0, KAN_BASE_SILU = 1 };
 enum { KAN_PASS_FORWARD = 0, KAN_PASS_BACKWARD = 1 };
 
 /* One bounded-grid layer (Eqs. "activation", "kanphi", "kanspline"): widths n_l, n_{l+1},
-   grid size G (cells), degree k (1..5; the specialised kernels cover k <= 3, degrees 4 and 5 run on the generic
-   ones), grid range.  base_act selects b(x) of Eq. "kanphi". */
+   grid size G (cells), degree k (1..5), grid range.  base_act selects b(x) of Eq. "kanphi". */
 typedef struct kan_layer_desc {
     int32_t n_in, n_out;
     int32_t G, k;

@@ -92,8 +92,9 @@ BackwardPlan backward_plan(const kan_layer_desc *d, int64_t B)
 {
     SplineGeom g = geom_of(d);
     BackwardPlan bp;
-    bp.wp = plan_walk(g, B, true);
-    bp.walk = bp.wp.ok != 0 && !high_degree(d);
+    // degrees 4 and 5 walk two four-row records per pair
+    bp.wp = plan_walk(g, B, true, high_degree(d));
+    bp.walk = bp.wp.ok != 0;
     bp.tail_bytes = 0;
     if (bp.walk) {
         bp.n_slabs = bp.wp.n_slabs;
@@ -232,7 +233,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
     const BackwardPlan bp = backward_plan(desc, B);
-    if (high_degree(desc)) {
+    if (high_degree(desc) && !bp.walk) {
         float *part_c = (float *)((char *)ws + folded_bytes(desc));
         float *part_b = (float *)((char *)part_c + (size_t)bp.n_slabs * folded_bytes(desc));
         return highk_backward(highk_of(desc), x, coef, w_s, w_b, gy, cf, gx, gcoef, gw_s, gw_b, part_c, part_b,

@@ -1,9 +1,10 @@
-// The generic kernels once more, for spline degrees 4 and 5 (window of 6 rows).  Everything in
-// kan_generic.hip is written against kMaxK; this translation unit compiles it with kMaxK = 6 in a
-// namespace of its own and exposes it through kan_highk.hpp.
+// The generic kernels and the row-stream forward kernel once more, for spline degrees 4 and 5 (window of
+// 6 rows).  Everything in kan_generic.hip and kan_rows.hip is written against kMaxK; this translation unit
+// compiles them with kMaxK = 6 in a namespace of its own and exposes them through kan_highk.hpp.
 #define KAN_MAXK 6
 #define KAN_NS kan_k5
 #include "kan_generic.hip"
+#include "kan_rows.hip"
 #include "kan_highk.hpp"
 
 namespace kan {
@@ -26,6 +27,7 @@ hipError_t highk_forward(const HighKLayer &l, const float *x, const float *coef,
     const kan_k5::SplineGeom g = geom_of(l);
     hipError_t e = kan_k5::launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st);
     if (e != hipSuccess) return e;
+    if (kan_k5::forward_rows_plan(g)) return kan_k5::launch_forward_rows(g, x, cf, y, B, st);
     return kan_k5::launch_forward_generic(g, x, cf, w_b, y, B, st);
 }
 

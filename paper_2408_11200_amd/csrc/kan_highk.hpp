@@ -22,4 +22,11 @@ hipError_t highk_backward(const HighKLayer &l, const float *x, const float *coef
                           const float *gy, float *cf, float *gx, float *gcoef, float *gw_s, float *gw_b,
                           float *part_c, float *part_b, int n_chunks, int64_t chunk_len, int64_t B, hipStream_t st);
 
+// Sorted records of the walk for degrees 4 and 5 (kan_walk_k5.hip): per (chunk of S samples, input) a list of
+// 2 S records in the four-row format of the walk, two per pair (rows 0..3 of its six-row window with the base
+// term; rows 4..5), sorted by first row.  xT is the transposed input [n_in][B]; rt / base / w4 (and dbase / dw4
+// when not null) are the record arrays, [chunk][input][2 S].  S: a power of two, 256 .. 4096.
+hipError_t highk_sorted_records(const HighKLayer &l, const float *xT, int64_t B, int S, int row_bits, int *rt,
+                                float *base, float *w4, float *dbase, float *dw4, hipStream_t st);
+
 }  // namespace kan

@@ -89,7 +89,7 @@ hipError_t launch_forward_lds_rows(const SplineGeom &g, const float *x, const fl
 // Sorted pair records of the walk, one per (sample, input) pair, as a structure of arrays indexed
 // [chunk][input][rank in the chunk's sorted order]: first row of the K-wide window (clamped into the
 // table; kRtRowBits bits) | the sample's index inside its chunk << kRtRowBits (chunks hold at most
-// 2^13 samples); the base value; the K window weights (16-byte
+// 2^13 samples; 2^12 for degrees 4 and 5, where bit 31 says which of a pair's two records this is); the base value; the K window weights (16-byte
 // aligned quadruples); and the same for the x-derivatives (null when dL/dx is not wanted).
 constexpr int kRtRowBits = 19;
 constexpr int kRtRowMask = (1 << kRtRowBits) - 1;
@@ -115,10 +115,14 @@ struct WalkPlan {
     int row_bits;        // bits of the largest window row (sort key width)
     int shared;          // 1: fewer partial slabs than chunks; the chunks are walked in rounds of n_slabs
     int n_slabs;         // partial slabs the walk writes: n_chunks, or what fits the budget when shared
+    int hk;              // 1: degrees 4 and 5.  A pair's window of six rows is walked as two records of four
+                         // rows (rows 0..3 with the base term, rows 4..5), so a sorted list has L = 2 S entries
+                         // and dL/dx is the sum of two partial results per output tile
+    int L;               // entries of one sorted list: S, or 2 S when hk
 };
 // allow_shared: tables whose per-chunk partial slabs would not fit the budget are still planned, with the
 // chunks taking turns on the slabs that fit (ok stays 0 for them otherwise).
-WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared = false);
+WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared = false, bool high_degree = false);
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out);
 hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const float *x, const float *gy,
                                 const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,

@@ -12,7 +12,7 @@
 #include "kan_device.hpp"
 #include "kan_launch.hpp"
 
-namespace kan {
+namespace KAN_NS {
 
 namespace {
 
@@ -106,15 +106,14 @@ __global__ __launch_bounds__(256) void forward_rows_kernel(SplineGeom g, const f
 #pragma unroll
                 for (int s = 0; s < kMaxK; ++s) load_t<T>(slab + s * g.n_out + o, c[s]);
                 load_t<T>(slab + g.rows * g.n_out + jc, wb);
-                const float w0 = row_bcast<N>(w[0]), w1 = row_bcast<N>(w[1]);
-                const float w2 = row_bcast<N>(w[2]), w3 = row_bcast<N>(w[3]);
+                float ws[kMaxK];
+#pragma unroll
+                for (int s = 0; s < kMaxK; ++s) ws[s] = row_bcast<N>(w[s]);
                 const float bs = row_bcast<N>(base);
 #pragma unroll
                 for (int r = 0; r < T; ++r) {
-                    acc[r] = fmaf(w0, c[0][r], acc[r]);
-                    acc[r] = fmaf(w1, c[1][r], acc[r]);
-                    acc[r] = fmaf(w2, c[2][r], acc[r]);
-                    acc[r] = fmaf(w3, c[3][r], acc[r]);
+#pragma unroll
+                    for (int s = 0; s < kMaxK; ++s) acc[r] = fmaf(ws[s], c[s][r], acc[r]);
                     acc[r] = fmaf(bs, wb[r], acc[r]);
                 }
             });
@@ -151,4 +150,4 @@ hipError_t launch_forward_rows(const SplineGeom &g, const float *x, const float 
     return hipGetLastError();
 }
 
-}  // namespace kan
+}  // namespace KAN_NS

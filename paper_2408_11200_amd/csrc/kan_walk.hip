@@ -35,6 +35,7 @@
 // VALU work.  None of the 256 multiply-adds of an instruction is padding.
 #include "kan_device.hpp"
 #include "kan_launch.hpp"
+#include "kan_highk.hpp"
 
 namespace kan {
 
@@ -192,17 +193,17 @@ __global__ __launch_bounds__(64 * NW) void cell_sort_kernel(SplineGeom g, const 
 // per (chunk, input, output).
 __global__ __launch_bounds__(256) void walk_carry_kernel(SplineGeom g, const int *__restrict__ rt,
                                                          const float *__restrict__ carry, float *__restrict__ part_c,
-                                                         int S, int n_chunks, int n_seg, int chunk0, int shared)
+                                                         int L, int n_chunks, int n_seg, int chunk0, int shared)
 {
     // n_chunks chunks starting at chunk0 of the batch; shared: the launch's chunk number l adds to slab l
     const int64_t at = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (at >= (int64_t)n_chunks * g.n_in * g.n_out) return;
     const int j = (int)(at % g.n_out);
     const int64_t ci = (int64_t)chunk0 * g.n_in + at / g.n_out;               // chunk * n_in + input
-    const int seg_len = S / n_seg;
+    const int seg_len = L / n_seg;              // L: entries per sorted list
     float *slab = part_c + (shared ? at / g.n_out : ci) * g.rows * g.n_out + j;
     for (int k = 1; k < n_seg; ++k) {
-        const int rf = rt[ci * S + (int64_t)k * seg_len] & kRtRowMask;
+        const int rf = rt[ci * L + (int64_t)k * seg_len] & kRtRowMask;
         const float *cr = carry + ((ci * n_seg + k) * kMaxK) * g.n_out + j;
         for (int s = 0; s < kMaxK; ++s)
             if (rf + s < g.rows) slab[(int64_t)(rf + s) * g.n_out] += cr[(int64_t)s * g.n_out];
@@ -237,10 +238,11 @@ int log2_exact(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
 
 // ---- planning and launch ---------------------------------------------------------------------
 
-WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared)
+WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared, bool high_degree)
 {
     WalkPlan p = {};
     if (g.rows < kMaxK || g.rows > kRtRowMask || B < 1) return p;
+    if (high_degree && g.rows < 6) return p;          // a six-row window must fit the table
     if (g.n_out % 8 == 0 && g.n_out > 256) {
         p.T = 8;            // one tile covers 512 outputs: the per-record work is shared by twice as many
         p.streams = 1;
@@ -260,14 +262,18 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared)
     //   - an eighth of the batch (one chunk per XCD at least),
     // then raised until the partial sums fit 2 GiB.  Few, long chunks keep the partial sums small;
     // the parallelism comes from cutting each sorted list into segments (below).
-    auto pow2_floor = [](int64_t v) { int64_t q = 256; while (q * 2 <= v && q < 8192) q *= 2; return (int)q; };
+    // (two records per pair for degrees 4 and 5: the sort holds 2 S keys and a record has 12 bits for the sample)
+    const int s_max = high_degree ? 4096 : 8192;
+    auto pow2_floor = [s_max](int64_t v) { int64_t q = 256; while (q * 2 <= v && q < s_max) q *= 2; return (int)q; };
     int S = pow2_floor((4ll << 20) / ((int64_t)g.n_out * 4));
     if (p.T == 8 && S > 1024) S = 1024;      // eight outputs per lane: stay with single-level sums (registers)
     const int s_b8 = pow2_floor(B / 8);
     S = S < s_b8 ? S : s_b8;
     const int64_t slab = (int64_t)g.n_in * g.rows * g.n_out * (int64_t)sizeof(float);
-    while (S < 8192 && ((B + S - 1) / S) * slab > (2ll << 30)) S *= 2;
+    while (S < s_max && ((B + S - 1) / S) * slab > (2ll << 30)) S *= 2;
     p.S = S;
+    p.hk = high_degree ? 1 : 0;
+    p.L = high_degree ? 2 * S : S;
     p.sbits = log2_exact(S);
     p.n_chunks = (int)((B + S - 1) / S);
     // segments per list: enough for about 2048 waves, at least 64 records each
@@ -279,7 +285,7 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared)
     p.n_slabs = p.n_chunks;
     auto plan_segments = [&](int chunks_per_launch) {
         p.n_seg = 1;
-        while (S / (p.n_seg * 2) >= 64 &&
+        while (p.L / (p.n_seg * 2) >= 64 &&
                (int64_t)chunks_per_launch * p.n_seg * p.n_jt * g.n_in < (int64_t)2048 * p.streams)
             p.n_seg *= 2;
     };
@@ -323,8 +329,9 @@ static size_t walk_carry_bytes(const WalkPlan &p, int n_in, int n_out)
 
 size_t walk_scratch_bytes(const WalkPlan &p, int64_t B, int n_in, int n_out)
 {
-    const size_t n = (size_t)p.n_chunks * n_in * p.S;
-    const size_t gxp = p.n_jt > 1 ? up256((size_t)p.n_jt * B * n_in * sizeof(float)) : 0;
+    const size_t n = (size_t)p.n_chunks * n_in * p.L;
+    const int n_part = p.n_jt * (p.hk ? 2 : 1);       // partial dL/dx results per (sample, input)
+    const size_t gxp = n_part > 1 ? up256((size_t)n_part * B * n_in * sizeof(float)) : 0;
     return up256((size_t)B * n_in * sizeof(float)) + 3 * up256(n * 4) + 2 * up256(n * 16) + gxp +
            walk_carry_bytes(p, n_in, n_out);
 }
@@ -357,7 +364,8 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
                                 const float *cf, const float *w_b, void *scratch, float *gx, float *part_c,
                                 float *part_b, int64_t B, hipStream_t st)
 {
-    const size_t n = (size_t)p.n_chunks * g.n_in * p.S;
+    const size_t n = (size_t)p.n_chunks * g.n_in * p.L;
+    const int n_part = p.n_jt * (p.hk ? 2 : 1);
     const bool dx = gx != nullptr;
     char *at = (char *)scratch;
     float *xT = (float *)at;            at += up256((size_t)B * g.n_in * sizeof(float));
@@ -367,11 +375,25 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
     rec.w4 = (float *)at;               at += up256(n * 16);
     rec.dbase = dx ? (float *)at : nullptr; at += up256(n * 4);
     rec.dw4 = dx ? (float *)at : nullptr;   at += up256(n * 16);
-    float *gx_part = (float *)at;       at += p.n_jt > 1 ? up256((size_t)p.n_jt * B * g.n_in * sizeof(float)) : 0;
+    float *gx_part = (float *)at;       at += n_part > 1 ? up256((size_t)n_part * B * g.n_in * sizeof(float)) : 0;
     float *carry = (float *)at;
-    if (hipError_t e = launch_sorted_records(g, x, xT, B, p.S, p.row_bits, rec, st); e != hipSuccess) return e;
+    if (p.hk) {
+        // degrees 4 and 5: the records come from the kernel built for a window of six rows
+        {
+            dim3 grid((unsigned)((B + 63) / 64), (unsigned)((g.n_in + 63) / 64));
+            prof::Timed tm("walk_transpose", st);
+            transpose_kernel<<<grid, 256, 0, st>>>(x, xT, B, g.n_in);
+        }
+        HighKLayer l;
+        l.n_in = g.n_in; l.n_out = g.n_out; l.rows = g.rows; l.k = g.k; l.lo = g.lo; l.inv_h = g.inv_h; l.base_act = g.base_act;
+        if (hipError_t e = highk_sorted_records(l, xT, B, p.S, p.row_bits, rec.rt, rec.base, rec.w4, rec.dbase, rec.dw4, st);
+            e != hipSuccess)
+            return e;
+    } else if (hipError_t e = launch_sorted_records(g, x, xT, B, p.S, p.row_bits, rec, st); e != hipSuccess) {
+        return e;
+    }
     const int bpc = (p.n_seg * p.n_jt * g.n_in + 4 * p.streams - 1) / (4 * p.streams);
-    float *gx_out = dx ? (p.n_jt > 1 ? gx_part : gx) : nullptr;
+    float *gx_out = dx ? (n_part > 1 ? gx_part : gx) : nullptr;
     // Sparse regime (far more rows than a chunk has samples): most rows of a chunk's partial slab
     // receive nothing.  The slab is zeroed with a streaming fill and the walk skips the gaps instead of
     // stepping through them row by row.  A shared slab is always used this way.
@@ -410,15 +432,15 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
         if (part_c != nullptr && p.n_seg > 1) {
             const int64_t nn = (int64_t)here * g.n_in * g.n_out;
             prof::Timed tm("walk_carry", st);
-            walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.S, here,
+            walk_carry_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(g, rec.rt, carry, part_c, p.L, here,
                                                                            p.n_seg, chunk0, p.shared);
         }
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }
-    if (dx && p.n_jt > 1) {
+    if (dx && n_part > 1) {
         const int64_t nn = B * g.n_in;
         prof::Timed tm("walk_gx_sum", st);
-        gx_sum_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(gx_part, gx, nn, p.n_jt);
+        gx_sum_kernel<<<(unsigned)((nn + 255) / 256), 256, 0, st>>>(gx_part, gx, nn, n_part);
     }
     return hipGetLastError();
 }

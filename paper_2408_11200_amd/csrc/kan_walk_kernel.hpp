@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
                                                             float *__restrict__ part_c, float *__restrict__ part_b,
                                                             float *__restrict__ gx, int64_t B, int S, int n_chunks,
                                                             int n_jt, int blocks_per_chunk, int xcd_groups, int prezeroed, int n_seg,
-                                                            float *__restrict__ carry, int chunk0, int shared)
+                                                            float *__restrict__ carry, int chunk0, int shared, int L, int hk)
 {
     constexpr int LPS = 64 / STREAMS;
     constexpr int RPW = LPS / 4;                    // records whose weights fit one register of a stream
@@ -158,13 +158,18 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
     const int i = ws % g.n_in;
     const int jt = (ws / g.n_in) % n_jt;
     const int seg = ws / (g.n_in * n_jt);
-    const int seg_len = S / n_seg;                  // a multiple of 16
+    // L entries per sorted list: S, or 2 S with two records per pair (hk); seg_len is a multiple of 16
+    const int seg_len = L / n_seg;
     const int j = (jt * LPS + q) * T;
     const bool jok = j < g.n_out;
     const int jc = jok ? j : 0;
     const int64_t b0 = (int64_t)c * S;
     const int n_c = (int)((B - b0) < S ? (B - b0) : S);
-    const int64_t list0 = ((int64_t)c * g.n_in + i) * S;
+    const int64_t list0 = ((int64_t)c * g.n_in + i) * L;
+    const int n_live = hk ? 2 * n_c : n_c;          // records that belong to real samples (they sort first)
+    // hk: 12 bits of sample index, bit 31 of a record (bit 12 after the shift) names the partial gx it adds to
+    const int smp_mask = hk ? 0xfff : 0x1fff;
+    const int64_t gx_second = (int64_t)n_jt * B * g.n_in;
     const int64_t list = list0 + (int64_t)seg * seg_len;        // this segment's records
     // The segment owns the table rows from its first record's row up to the next segment's first
     // row; what its window holds beyond that at the end goes to the next segment's carry rows.
@@ -302,10 +307,11 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
             load_vec<T>(gyp + (int64_t)t * g.n_out, dst[N]);
         });
     };
-    gather((int)((unsigned)mine.rt >> kRtRowBits), std::integral_constant<int, 0>{}, gbuf[0]);
+    gather((int)((unsigned)mine.rt >> kRtRowBits) & smp_mask, std::integral_constant<int, 0>{}, gbuf[0]);
     for (int bi = 0; bi < nb; ++bi) {
         const Batch upcoming = load_batch(bi + 1 < nb ? bi + 1 : bi);
-        const int rowv = mine.rt & kRtRowMask, tv = (int)((unsigned)mine.rt >> kRtRowBits);
+        const int rowv = mine.rt & kRtRowMask, tvf = (int)((unsigned)mine.rt >> kRtRowBits);
+        const int tv = tvf & smp_mask;
         float dot[16];
         bool quad_same = false;
         // The 16 records go in groups of four.  The gy rows of the next group (the first of the next
@@ -315,7 +321,7 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
             constexpr int H = decltype(h)::value;
             auto &gr = gbuf[H & 1];
             if constexpr (H + 1 < 16 / GROUP) gather(tv, std::integral_constant<int, H + 1>{}, gbuf[(H + 1) & 1]);
-            else gather((int)((unsigned)upcoming.rt >> kRtRowBits), std::integral_constant<int, 0>{}, gbuf[0]);
+            else gather((int)((unsigned)upcoming.rt >> kRtRowBits) & smp_mask, std::integral_constant<int, 0>{}, gbuf[0]);
             static_for<0, GROUP>([&](auto n) {
                 constexpr int N = decltype(n)::value;
                 constexpr int R = H * GROUP + N;
@@ -392,8 +398,10 @@ __global__ __launch_bounds__(256) void backward_walk_kernel(SplineGeom g, WalkRe
         if constexpr (DX) {
             const float total = reduce_levels<LPS / 2, 16>(dot, lane);
             const int qn = quantity_of<LPS>(lane);
-            const int t = __shfl(tv, (lane & ~15) | qn, 64);
-            if ((lane % (LPS / 16)) == 0 && seg * seg_len + bi * 16 + qn < n_c) gxo[(int64_t)t * g.n_in] = total;
+            const int tf = __shfl(tvf, (lane & ~15) | qn, 64);
+            const int t = tf & smp_mask;
+            float *gxr = gxo + ((tf >> 12) & hk ? gx_second : 0);
+            if ((lane % (LPS / 16)) == 0 && seg * seg_len + bi * 16 + qn < n_live) gxr[(int64_t)t * g.n_in] = total;
         }
         if constexpr (FOLD) {
             if ((bi & 15) == 15) {
@@ -441,7 +449,7 @@ void walk_launch(bool dx, unsigned blocks, hipStream_t st, const SplineGeom &g, 
                    : (p.S > 1024 ? backward_walk_kernel<STREAMS, T, false, true> : backward_walk_kernel<STREAMS, T, false, false>);
     // the first round of a shared run finds its slabs zero and stores like an unshared run
     kern<<<blocks, 256, 0, st>>>(g, rec, gy, cf, w_b, part_c, part_b, gx, B, p.S, n_chunks, p.n_jt, bpc, m, prezeroed,
-                                 p.n_seg, carry, chunk0, (p.shared && chunk0 > 0) ? 1 : 0);
+                                 p.n_seg, carry, chunk0, (p.shared && chunk0 > 0) ? 1 : 0, p.L, p.hk);
 }
 
 }  // namespace

@@ -93,9 +93,34 @@ def test_layer_parity_sweep(B, n_in, n_out, G, k, outside):
     (300, 7, 96, 9, 4, 0.2), (513, 5, 33, 12, 5, 0.25), (64, 3, 256, 40, 5, 0.1), (1000, 4, 8, 6, 4, 0.3),
 ])
 def test_layer_parity_degrees_four_and_five(B, n_in, n_out, G, k, outside):
-    """Degrees 4 and 5 (window of 5 and 6 rows) run on the generic kernels."""
+    """Degrees 4 and 5 (window of 5 and 6 rows)."""
     w = workloads.random_kan_layer(4000 + B, B, n_in, n_out, G, k, outside_frac=outside)
     run_layer_parity(w)
+
+
+@pytest.mark.parametrize("B,n_in,n_out,G,k,outside", [
+    (2100, 3, 132, 40, 4, 0.2),        # one stream per wave, ragged output tile, three ragged chunks
+    (900, 6, 96, 7, 5, 0.3),           # two streams per wave
+    (300, 9, 12, 30, 4, 0.1),          # four streams per wave
+    (300, 9, 10, 30, 5, 0.1),          # narrow layer, one output per lane
+    (130, 4, 520, 10, 5, 0.1),         # eight outputs per lane, two output tiles: four partial dL/dx
+    (700, 5, 32, 3000, 4, 0.1),        # far more rows than samples: pre-zeroed partial tables, gap jumps
+    (9000, 2, 64, 1, 5, 0.5),          # six rows in all: every window is clamped; two chunks of 4096 + a ragged one
+    (64, 2, 8, 1, 4, 0.3),             # five rows: fewer than a six-row window, generic kernels
+])
+def test_high_degree_backward_as_two_records_per_pair(B, n_in, n_out, G, k, outside):
+    """Degrees 4 and 5 on the sorted walk: each pair's six-row window is walked as two four-row records
+    (rows 0..3 with the base term, rows 4..5); dL/dx is the sum of the two partial results.  Also
+    bit-reproducible."""
+    w = workloads.random_kan_layer(4200 + B + k, B, n_in, n_out, G, k, outside_frac=outside)
+    run_layer_parity(w)
+    s, p = w.layers[0], w.params[0]
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    a = binding.kan_backward(s, x, coef, w_s, w_b, gy)
+    b = binding.kan_backward(s, x, coef, w_s, w_b, gy, want=("gx",))
+    c = binding.kan_backward(s, x, coef, w_s, w_b, gy, want=("gcoef", "gw_b"))
+    assert torch.equal(a["gx"], b["gx"])
+    assert torch.equal(a["gcoef"], c["gcoef"]) and torch.equal(a["gw_b"], c["gw_b"])
 
 
 def test_half_gigabyte_table_wide_layer():

@@ -158,6 +158,7 @@ static int forward_impl(const kan_layer_desc *desc, int64_t B, const float *x, c
         return highk_forward(highk_of(desc), x, coef, w_s, w_b, cf, y, B, st) == hipSuccess ? KAN_OK : KAN_ERR_HIP;
     if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
     hipError_t e = narrow_applicable(g)    ? launch_forward_narrow(g, x, cf, w_b, y, B, st)
+                   : (g.n_out <= 64 && forward_lds_rows_plan(g, B)) ? launch_forward_lds_rows(g, x, cf, y, B, st)
                    : forward_rows_plan(g) ? launch_forward_rows(g, x, cf, y, B, st)
                    : forward_lds_plan(g)  ? launch_forward_lds(g, x, cf, y, B, st)
                    : forward_lds_rows_plan(g, B) ? launch_forward_lds_rows(g, x, cf, y, B, st)

@@ -246,6 +246,9 @@ WalkPlan plan_walk(const SplineGeom &g, int64_t B, bool allow_shared, bool high_
     if (g.n_out % 8 == 0 && g.n_out > 256) {
         p.T = 8;            // one tile covers 512 outputs: the per-record work is shared by twice as many
         p.streams = 1;
+    } else if (g.n_out % 2 == 0 && g.n_out > 16 && g.n_out <= 32) {
+        p.T = 2;            // 16 lanes x 2 outputs cover the layer: no idle lanes in a stream
+        p.streams = 4;
     } else if (g.n_out % 4 == 0) {
         p.T = 4;
         p.streams = g.n_out > 128 ? 1 : (g.n_out > 64 ? 2 : 4);
@@ -313,6 +316,7 @@ KAN_WALK_VARIANT(walk_launch_s1t8);
 KAN_WALK_VARIANT(walk_launch_s1t4);
 KAN_WALK_VARIANT(walk_launch_s2t4);
 KAN_WALK_VARIANT(walk_launch_s4t4);
+KAN_WALK_VARIANT(walk_launch_s4t2);
 KAN_WALK_VARIANT(walk_launch_s4t1);
 #undef KAN_WALK_VARIANT
 
@@ -424,6 +428,8 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
                 walk_launch_s2t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else if (p.T == 4 && p.streams == 4)
                 walk_launch_s4t4(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
+            else if (p.T == 2 && p.streams == 4)
+                walk_launch_s4t2(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else if (p.T == 1 && p.streams == 4)
                 walk_launch_s4t1(dx, blocks, st, g, rec, gy, cf, w_b, part_c, part_b, gx_out, B, p, bpc, m, prezeroed, carry, chunk0, here);
             else

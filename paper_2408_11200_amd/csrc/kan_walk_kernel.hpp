@@ -87,8 +87,11 @@ __device__ __forceinline__ void load_vec(const float *p, float (&v)[T])
     } else if constexpr (T == 4) {
         const float4 t = *reinterpret_cast<const float4 *>(p);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else if constexpr (T == 2) {
+        const float2 t = *reinterpret_cast<const float2 *>(p);
+        v[0] = t.x; v[1] = t.y;
     } else {
-        static_assert(T == 1, "one, four or eight outputs per lane");
+        static_assert(T == 1, "one, two, four or eight outputs per lane");
         v[0] = *p;
     }
 }
@@ -100,6 +103,8 @@ __device__ __forceinline__ void store_vec(float *p, const float (&v)[T])
         *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
     } else if constexpr (T == 4) {
         *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    } else if constexpr (T == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
     } else {
         p[0] = v[0];
     }

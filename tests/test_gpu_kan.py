@@ -78,6 +78,8 @@ SWEEP = [
     (300, 9, 12, 30, 3, 0.1),          # narrow layer, one output per lane
     (700, 5, 32, 3000, 3, 0.1),        # far more rows than samples: pre-zeroed partial slabs, gap jumps
     (1500, 3, 256, 2500, 2, 0.05),     # the same with one stream per wave
+    (400, 6, 18, 12, 3, 0.2),          # two outputs per lane in the walk, ragged stream (18 of 32 lanes' outputs)
+    (1300, 3, 30, 25, 2, 0.1),         # the same, 30 outputs
     (64, 2, 8, 70000, 3, 0.1),         # 17-bit row numbers in the sorted records (three sort digits)
     (64, 2, 8, 600000, 3, 0.1),        # more rows than the sorted path indexes (2^19): generic kernels
 ]

@@ -310,11 +310,17 @@ __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const 
     for (int m = 0; m < kRowBlock; ++m)
 #pragma unroll
         for (int r = 0; r < R; ++r) acc[m * TJ + lane * R + r] = 0.0f;
-    float accb[R];
+    // the base sums go in two levels (accb is folded into accb_hi every 256 samples) so that a chunk of a
+    // thousand O(1) terms keeps fp32 accuracy
+    float accb[R], accb_hi[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) accb[r] = 0.0f;
+    for (int r = 0; r < R; ++r) { accb[r] = 0.0f; accb_hi[r] = 0.0f; }
 
     for (int64_t b0 = b_lo; b0 < b_hi; b0 += kWave) {
+        if (((b0 - b_lo) & 255) == 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) { accb_hi[r] += accb[r]; accb[r] = 0.0f; }
+        }
         const int64_t my_b = (b0 + lane < b_hi) ? b0 + lane : b_hi - 1;
         Pair p = pair_eval<false>(x[my_b * g.n_in + i], g, i);
         const int n_b = (b_hi - b0 < kWave) ? (int)(b_hi - b0) : kWave;
@@ -353,7 +359,11 @@ __global__ __launch_bounds__(64) void dparam_generic_kernel(SplineGeom g, const 
         for (int r = 0; r < R; ++r) a[r] = acc[(m - lo) * TJ + lane * R + r];
         store_vec<R>(pc + (int64_t)m * g.n_out, a);
     }
-    if (part_b) store_vec<R>(part_b + (((int64_t)blockIdx.z * n_rb + rb) * g.n_in + i) * g.n_out + j, accb);
+    if (part_b) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) accb[r] += accb_hi[r];
+        store_vec<R>(part_b + (((int64_t)blockIdx.z * n_rb + rb) * g.n_in + i) * g.n_out + j, accb);
+    }
 }
 
 // Stage 2.  Sum the partial sums (n_chunks slabs for the coefficient rows, n_slices_b slices for the

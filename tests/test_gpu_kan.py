@@ -109,6 +109,7 @@ def test_layer_parity_degrees_four_and_five(B, n_in, n_out, G, k, outside):
     (700, 5, 32, 3000, 4, 0.1),        # far more rows than samples: pre-zeroed partial tables, gap jumps
     (9000, 2, 64, 1, 5, 0.5),          # six rows in all: every window is clamped; two chunks of 4096 + a ragged one
     (64, 2, 8, 1, 4, 0.3),             # five rows: fewer than a six-row window, generic kernels
+    (9000, 9, 132, 1, 4, 0.3),         # the same with chunks of a thousand samples in one cell (two-level base sums)
 ])
 def test_high_degree_backward_as_two_records_per_pair(B, n_in, n_out, G, k, outside):
     """Degrees 4 and 5 on the sorted walk: each pair's six-row window is walked as two four-row records

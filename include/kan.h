@@ -15,8 +15,9 @@
  *     declared); scratch space comes in through (ws, ws_bytes) and must be at
  *     least what the matching *_workspace_bytes call returns (256-byte aligned).
  *   - `stream` is a hipStream_t passed as void*.  All work is enqueued on it.
- *     kan_* calls never synchronise; the ukan_* calls synchronise the stream
- *     once to read back the group span (4 bytes), see below.
+ *     kan_* calls never synchronise; ukan_cg_forward, ukan_cg_backward and
+ *     ukan_cg_forward_saved synchronise the stream once to read back the group
+ *     span (4 bytes), see below; the other ukan_* calls do not.
  *   - Every float array must be 16-byte aligned (KAN_ERR_INVALID_ARG otherwise).
  *   - Row-major layouts:  x[B][n_in]  y,gy[B][n_out]  gx[B][n_in]
  *       coef,gcoef[n_in][G+k][n_out]   w_s,w_b,gw_s,gw_b[n_in][n_out]
@@ -187,6 +188,15 @@ size_t ukan_saved_bytes(const ukan_layer_desc *desc, int32_t max_groups);
 int ukan_cg_forward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
                           float *y, int32_t max_groups, void *saved, size_t saved_bytes, int32_t *span,
                           void *ws, size_t ws_bytes, void *stream);
+/* ukan_cg_forward_saved without the read-back: the caller states how many groups per input to provide for
+   (n_groups, 2 .. max_groups: e.g. the span an earlier call reported plus a margin) and the call only
+   enqueues kernels, so it can be captured in a HIP graph.  It writes 1 to *overflow (DEVICE memory, one
+   int32) when some input of this batch spans more groups than n_groups, else 0; with 1, y and `saved` are
+   not valid (samples beyond the provided groups contributed nothing) and the call should be repeated with a
+   larger n_groups.  Hand n_groups to ukan_cg_backward_saved as its span. */
+int ukan_cg_forward_saved_async(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
+                                float *y, int32_t max_groups, int32_t n_groups, void *saved, size_t saved_bytes,
+                                int32_t *overflow, void *ws, size_t ws_bytes, void *stream);
 int ukan_cg_backward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,
                            const float *gy, float *gx, const ukan_grads *g, int32_t max_groups,
                            const void *saved, size_t saved_bytes, int32_t span, void *ws, size_t ws_bytes,

@@ -25,7 +25,7 @@ PASS_FORWARD, PASS_BACKWARD = 0, 1
 EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
            "kan_static_scratch_bytes", "kan_forward_static", "kan_set_launch_observer",
            "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_saved_bytes",
-           "ukan_cg_forward_saved", "ukan_cg_backward_saved", "ukan_materialize_workspace_bytes",
+           "ukan_cg_forward_saved", "ukan_cg_forward_saved_async", "ukan_cg_backward_saved", "ukan_materialize_workspace_bytes",
            "ukan_materialize", "ukan_group_index"]
 
 
@@ -106,6 +106,9 @@ def load():
     lib.ukan_cg_forward_saved.restype = ctypes.c_int
     lib.ukan_cg_forward_saved.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, i32,
                                           vp, sz, ctypes.POINTER(i32), vp, sz, vp]
+    lib.ukan_cg_forward_saved_async.restype = ctypes.c_int
+    lib.ukan_cg_forward_saved_async.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, i32,
+                                                i32, vp, sz, vp, vp, sz, vp]
     lib.ukan_cg_backward_saved.restype = ctypes.c_int
     lib.ukan_cg_backward_saved.argtypes = [ctypes.POINTER(UkanLayerDesc), i64, vp, ctypes.POINTER(UkanParams), vp, vp,
                                            ctypes.POINTER(UkanGrads), i32, vp, sz, i32, vp, sz, vp]
@@ -403,6 +406,20 @@ def ukan_cg_forward_saved(spec, x, p, max_groups, saved=None, y=None, ws=None, s
     if rc != KAN_OK:
         raise KanError(rc, "ukan_cg_forward_saved")
     return y, saved, int(span.value)
+
+
+def ukan_cg_forward_saved_async(spec, x, p, max_groups, n_groups, saved, overflow, y, ws, stream=None):
+    """ukan_cg_forward_saved for a caller-stated span: no read-back, no allocation (every buffer is passed
+    in); overflow is a device int32 tensor of one element that receives 1 when n_groups was too small."""
+    d = ukan_desc(spec)
+    pp = _ukan_params(p)
+    assert overflow.dtype == torch.int32 and overflow.numel() >= 1
+    rc = load().ukan_cg_forward_saved_async(ctypes.byref(d), x.shape[0], _f32(x), ctypes.byref(pp), _f32(y), max_groups,
+                                            int(n_groups), _ptr(saved), saved.numel(), _ptr(overflow), _ptr(ws),
+                                            ws.numel(), _stream(stream))
+    if rc != KAN_OK:
+        raise KanError(rc, "ukan_cg_forward_saved_async")
+    return y
 
 
 def ukan_cg_backward(spec, x, p, gy, max_groups, want=None, out=None, ws=None, stream=None, saved=None, span=None):

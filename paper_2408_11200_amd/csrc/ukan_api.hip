@@ -143,8 +143,11 @@ void spline_geom(const ukan_layer_desc *d, int span, const int32_t *cell_base, S
 // steps 1-2 of the pass: group range, read-back, CG forward into the table(s)
 // With `saved` the products go to the caller's buffer (laid out for the span found) and z, pre and
 // the unscaled table are kept whatever the pass.
+// With provided_span > 0 nothing is read back: the table is built for that many groups per input and
+// *overflow (device) says whether the batch needed more.
 int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_params *p, int32_t max_groups,
-            char *ws, int pass, hipStream_t st, Prepared *out, char *saved = nullptr)
+            char *ws, int pass, hipStream_t st, Prepared *out, char *saved = nullptr, int32_t provided_span = 0,
+            int32_t *overflow = nullptr)
 {
     const int K = d->k + 1;
     const float inv_h = 1.0f / d->h;
@@ -158,9 +161,13 @@ int prepare(const ukan_layer_desc *d, int64_t B, const float *x, const ukan_para
     int32_t *cell_base = (int32_t *)(saved ? saved + S0.cell_base : ws + L0.cell_base);
     if (launch_range(x, B, d->n_in, inv_h, K, cmin, cmax, g_first, n_groups, cell_base, summary, st) != hipSuccess)
         return KAN_ERR_HIP;
-    int32_t span = 0;
-    if (hipMemcpyAsync(&span, summary, sizeof(span), hipMemcpyDeviceToHost, st) != hipSuccess) return KAN_ERR_HIP;
-    if (hipStreamSynchronize(st) != hipSuccess) return KAN_ERR_HIP;
+    int32_t span = provided_span;
+    if (provided_span > 0) {
+        if (launch_span_check(summary, provided_span, overflow, st) != hipSuccess) return KAN_ERR_HIP;
+    } else {
+        if (hipMemcpyAsync(&span, summary, sizeof(span), hipMemcpyDeviceToHost, st) != hipSuccess) return KAN_ERR_HIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return KAN_ERR_HIP;
+    }
     if (span < 2 || span > max_groups) return KAN_ERR_RANGE;
     out->n_g = span;
     out->L = make_layout(d, B, span, out->cp.n_chunks, record_bytes_for(d, B, max_groups), b_slices_for(d, B, max_groups), pass);
@@ -228,14 +235,15 @@ extern "C" size_t ukan_workspace_bytes(const ukan_layer_desc *desc, int64_t B, i
 
 namespace {
 int forward_impl(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p, float *y,
-                 int32_t max_groups, void *ws, size_t ws_bytes, void *stream, char *saved, int32_t *span)
+                 int32_t max_groups, void *ws, size_t ws_bytes, void *stream, char *saved, int32_t *span,
+                 int32_t provided_span = 0, int32_t *overflow = nullptr)
 {
     int rc = check_common(desc, B, x, p, max_groups, ws, ws_bytes, KAN_PASS_FORWARD);
     if (rc != KAN_OK || B == 0) return rc;
     if (!y || ((uintptr_t)y % 16) != 0) return KAN_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     Prepared pr;
-    rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr, saved);
+    rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr, saved, provided_span, overflow);
     if (rc != KAN_OK) return rc;
     if (span) *span = pr.n_g;
     hipError_t e = narrow_applicable(pr.g)            ? launch_forward_narrow(pr.g, x, pr.cf, p->w_b, y, B, st)
@@ -281,6 +289,19 @@ extern "C" int ukan_cg_forward_saved(const ukan_layer_desc *desc, int64_t B, con
     if (need == 0) return check_desc(desc) != KAN_OK ? check_desc(desc) : KAN_ERR_INVALID_ARG;
     if (B > 0 && (!saved || ((uintptr_t)saved % kAlign) != 0 || saved_bytes < need)) return KAN_ERR_WORKSPACE;
     return forward_impl(desc, B, x, p, y, max_groups, ws, ws_bytes, stream, (char *)saved, span);
+}
+
+extern "C" int ukan_cg_forward_saved_async(const ukan_layer_desc *desc, int64_t B, const float *x,
+                                           const ukan_params *p, float *y, int32_t max_groups, int32_t n_groups,
+                                           void *saved, size_t saved_bytes, int32_t *overflow, void *ws,
+                                           size_t ws_bytes, void *stream)
+{
+    const size_t need = ukan_saved_bytes(desc, max_groups);
+    if (need == 0) return check_desc(desc) != KAN_OK ? check_desc(desc) : KAN_ERR_INVALID_ARG;
+    if (n_groups < 2 || n_groups > max_groups) return KAN_ERR_RANGE;
+    if (B > 0 && (!overflow || ((uintptr_t)overflow % 4) != 0)) return KAN_ERR_INVALID_ARG;
+    if (B > 0 && (!saved || ((uintptr_t)saved % kAlign) != 0 || saved_bytes < need)) return KAN_ERR_WORKSPACE;
+    return forward_impl(desc, B, x, p, y, max_groups, ws, ws_bytes, stream, (char *)saved, nullptr, n_groups, overflow);
 }
 
 extern "C" int ukan_cg_backward_saved(const ukan_layer_desc *desc, int64_t B, const float *x, const ukan_params *p,

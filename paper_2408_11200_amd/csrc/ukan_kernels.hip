@@ -80,6 +80,12 @@ __global__ __launch_bounds__(256) void range_finalize_kernel(const int32_t *__re
     if (threadIdx.x == 0) summary[0] = widest[0] > INT_MAX ? INT_MAX : (int)widest[0];
 }
 
+// overflow[0] = 1 when the widest span found exceeds what the caller provided for, else 0
+__global__ void span_check_kernel(const int32_t *__restrict__ summary, int provided, int32_t *__restrict__ overflow)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) overflow[0] = summary[0] > provided ? 1 : 0;
+}
+
 // ---- CG input and hidden layer -------------------------------------------------
 // Row (i, t) of the generator batch is group g_first[i] + t of input i.  One block per
 // row: z = [E[i] ; PE(g)] (PE evaluated in fp64, rounded to fp32),
@@ -378,6 +384,12 @@ hipError_t launch_range(const float *x, int64_t B, int n_in, float inv_h, int K,
         range_kernel<<<grid, 256, 0, st>>>(x, cmin, cmax, B, n_in, inv_h);
         range_finalize_kernel<<<1, 256, 0, st>>>(cmin, cmax, g_first, n_groups, cell_base, summary, n_in, K);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_span_check(const int32_t *summary, int provided, int32_t *overflow, hipStream_t st)
+{
+    span_check_kernel<<<1, 64, 0, st>>>(summary, provided, overflow);
     return hipGetLastError();
 }
 

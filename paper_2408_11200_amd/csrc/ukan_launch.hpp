@@ -30,6 +30,7 @@ hipError_t launch_group_index(const float *x, int32_t *cell, int32_t *grp, int32
                               int K, hipStream_t st);
 hipError_t launch_range(const float *x, int64_t B, int n_in, float inv_h, int K, int32_t *cmin, int32_t *cmax,
                         int32_t *g_first, int32_t *n_groups, int32_t *cell_base, int32_t *summary, hipStream_t st);
+hipError_t launch_span_check(const int32_t *summary, int provided, int32_t *overflow, hipStream_t st);
 hipError_t launch_cg_hidden(const float *E, const float *W1, const float *b1, const int32_t *g_first, float *z,
                             float *pre, float *hid, int n_in, int n_g, int d_pe, int d_feat, int d_hid,
                             hipStream_t st);

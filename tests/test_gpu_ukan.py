@@ -208,6 +208,78 @@ def test_ukan_saved_errors():
     torch.cuda.synchronize()
 
 
+def test_ukan_forward_without_read_back_and_graph_capture():
+    """ukan_cg_forward_saved_async builds the table for a caller-stated number of groups and reports through a
+    device flag whether that was enough; with the exact span it equals the synchronising call bit for bit, with
+    a margin it still matches the oracle, with too few groups the flag is set.  The pair async forward + saved
+    backward only enqueues kernels, so a step can be captured in a HIP graph and replayed."""
+    spec, p, x, gy = make(31, 2500, 12, 256)
+    pd = {n: dev(a) for n, a in p.items()}
+    xd, gyd = dev(x), dev(gy)
+    mg = 64
+    y_ref, saved_ref, span = binding.ukan_cg_forward_saved(spec, xd, pd, mg)
+    g_ref = binding.ukan_cg_backward_saved(spec, xd, pd, gyd, mg, saved_ref, span)
+    saved = torch.empty(binding.ukan_saved_bytes(spec, mg), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(binding.ukan_workspace_bytes(spec, 2500, mg, binding.PASS_FORWARD), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(binding.ukan_workspace_bytes(spec, 2500, mg, binding.PASS_BACKWARD), dtype=torch.uint8, device="cuda")
+    flag = torch.full((1,), 9, dtype=torch.int32, device="cuda")
+    y = torch.empty_like(y_ref)
+    out = {n: torch.empty_like(t) for n, t in g_ref.items()}
+
+    def step(n_groups):
+        binding.ukan_cg_forward_saved_async(spec, xd, pd, mg, n_groups, saved, flag, y, ws_f)
+        binding.ukan_cg_backward_saved(spec, xd, pd, gyd, mg, saved, n_groups, out=out, ws=ws_b)
+
+    step(span)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0 and torch.equal(y, y_ref)
+    for n in out:
+        assert torch.equal(out[n], g_ref[n]), n
+    # a margin of five groups: same function, slightly different table extent
+    step(span + 5)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    inv_h = oracle.inv_h_of_spacing(spec.h)
+    assert_close(y, oracle.ukan_forward(x, p, spec.k, inv_h, spec.base_act), FWD_TOL, "y with a margin")
+    ref = oracle.ukan_backward(x, p, gy, spec.k, inv_h, spec.base_act)
+    for name in ref:
+        assert_close(out[name], ref[name], GRAD_TOL, name + " with a margin")
+    # too few groups: reported, nothing faults
+    if span > 2:
+        binding.ukan_cg_forward_saved_async(spec, xd, pd, mg, span - 1, saved, flag, y, ws_f)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1
+    with pytest.raises(binding.KanError) as e:
+        binding.ukan_cg_forward_saved_async(spec, xd, pd, mg, mg + 1, saved, flag, y, ws_f)
+    assert e.value.status == binding.KAN_ERR_RANGE
+    # one step as a graph, replayed with eager work in between and with new inputs before the last replay
+    step(span + 5)
+    torch.cuda.synchronize()
+    want = [y.clone()] + [out[n].clone() for n in sorted(out)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(span + 5)
+    for _ in range(3):
+        y.zero_()
+        for t in out.values():
+            t.fill_(3.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip([y] + [out[n] for n in sorted(out)], want):
+            assert torch.equal(a, b)
+        binding.ukan_cg_forward(spec, xd, pd, mg)
+    xd.mul_(0.9)
+    step(span + 5)
+    torch.cuda.synchronize()
+    want2 = [y.clone()] + [out[n].clone() for n in sorted(out)]
+    graph.replay()
+    torch.cuda.synchronize()
+    for a, b in zip([y] + [out[n] for n in sorted(out)], want2):
+        assert torch.equal(a, b)
+    assert int(flag.item()) == 0
+
+
 def test_ukan_backward_bit_reproducible():
     spec, p, x, gy = make(9, 2000, 12, 128)
     pd = {n: dev(a) for n, a in p.items()}

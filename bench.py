@@ -271,8 +271,8 @@ class UkanCase:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "p"],
                     help="c1..c5: the benchmark configurations; p: the paper's 32->32, N=2^17 shape (see --grid)")
     ap.add_argument("--grid", type=int, default=64, help="grid size G of workload p")

@@ -95,3 +95,28 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_workspace_planning_limits(lib):
+    """Host-side planning seen through the workspace queries: unsupported shapes report 0 bytes, tables too large
+    for one partial table per chunk stay within the partial-table budget, and the degree-5 backward pass (two
+    records per pair) asks for about twice the record space of the cubic one."""
+    lib.kan_workspace_bytes.restype = ctypes.c_size_t
+    lib.kan_workspace_bytes.argtypes = [ctypes.POINTER(binding.KanLayerDesc), ctypes.c_int64, ctypes.c_int]
+    ws = lambda *a, B=1 << 17, which=binding.PASS_BACKWARD: lib.kan_workspace_bytes(
+        ctypes.byref(binding.KanLayerDesc(*a)), B, which)
+    assert ws(70000, 8, 5, 3, -1.0, 1.0, 1) == 0                       # more inputs than a launch dimension holds
+    assert ws(4, 1 << 20, 1 << 12, 3, -1.0, 1.0, 1) == 0              # a table row range beyond 32-bit offsets
+    assert ws(32, 32, 64, 6, -1.0, 1.0, 1) == 0                        # degree 6
+    table = lambda G: 32 * (G + 4) * 32 * 4
+    small, huge = ws(32, 32, 1 << 15, 3, -1.0, 1.0, 1), ws(32, 32, 1 << 18, 3, -1.0, 1.0, 1)
+    assert small > 16 * table(1 << 15)                                  # one partial table per chunk of 8192 samples
+    assert table(1 << 18) * 3 < huge < 5 << 30                          # shared partial tables: about 4 GiB, not 16 tables
+    k3, k5 = ws(32, 32, 64, 3, -1.0, 1.0, 1, B=1 << 16), ws(32, 32, 64, 5, -1.0, 1.0, 1, B=1 << 16)
+    assert 1.7 * k3 < k5 < 2.3 * k3
+    lib.ukan_saved_bytes.restype = ctypes.c_size_t
+    lib.ukan_saved_bytes.argtypes = [ctypes.POINTER(binding.UkanLayerDesc), ctypes.c_int32]
+    u = binding.UkanLayerDesc(128, 256, 3, 0.25, 32, 32, 64, 0)
+    assert lib.ukan_saved_bytes(ctypes.byref(u), 1) == 0
+    a, b = lib.ukan_saved_bytes(ctypes.byref(u), 64), lib.ukan_saved_bytes(ctypes.byref(u), 128)
+    assert 2 * 128 * 64 * 4 * 256 * 4 < a < b < 2.1 * a

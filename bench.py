@@ -379,7 +379,10 @@ def main():
     launches = {n: cnt / psteps for n, (tot, cnt) in kt.items()}
     dom = max(per_step, key=per_step.get) if per_step else None
     dom_ms = per_step[dom] if dom else None
-    if dom in KERNEL_ROLE and isinstance(case, KanCase):
+    # a stack of layers: the figure is meaningful when the dominant kernel family runs once on every layer
+    # (then it carries its share of the work of all the edges); otherwise it is left out
+    n_layers = len(case.w.layers)
+    if dom in KERNEL_ROLE and (isinstance(case, KanCase) or round(launches[dom]) == n_layers):
         flops = flops_per_edge(case.k) * ROLE_SHARE[KERNEL_ROLE[dom]] * edges
         achieved = flops / (dom_ms * 1e-3) / 1e12
     else:

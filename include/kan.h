@@ -113,8 +113,8 @@ int kan_forward(const kan_layer_desc *desc, int64_t B, const float *x, const flo
      gcoef[i][m][j] = w_s[i][j] sum_b gy[b][j] N_{m-idx(b,i)}(u(b,i))
      gw_s[i][j]     = sum_b gy[b][j] spline_ij(x[b][i])
      gw_b[i][j]     = sum_b gy[b][j] silu(x[b][i])
-   The batch reduction is atomic-free and runs in a fixed order: repeated calls give
-   bit-identical gradients. */
+   The batch reduction runs in a fixed order (no atomics whose order could vary): repeated
+   calls give bit-identical gradients. */
 int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
                  const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
                  float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream);

@@ -84,13 +84,16 @@ class KanCase:
         self.edges = B * s.n_in * s.n_out
         self.k = s.k
         self.config = {"workload": w.name, "B": B, "n_in": s.n_in, "n_out": s.n_out, "G": s.G, "k": s.k,
-                       "grid": [s.grid_lo, s.grid_hi], "pass": "forward+backward"}
+                       "grid": [s.grid_lo, s.grid_hi], "pass": "forward+backward",
+                       "hand_off": "the backward pass reads the scale-folded table the forward pass left in its workspace"}
 
     def forward(self):
         self.binding.kan_forward(self.s, self.x, self.coef, self.w_s, self.w_b, y=self.y, ws=self.ws_f)
 
     def backward(self):
-        self.binding.kan_backward(self.s, self.x, self.coef, self.w_s, self.w_b, self.gy, out=self.out, ws=self.ws_b)
+        # the backward pass of a step reads the scale-folded table its forward pass left in ws_f
+        self.binding.kan_backward_saved(self.s, self.x, self.coef, self.w_s, self.w_b, self.gy, self.ws_f, out=self.out,
+                                        ws=self.ws_b)
 
     def step(self):
         self.forward()
@@ -148,8 +151,8 @@ class KanStackCase:
         self.torch.sub(self.acts[-1], self.target, out=self.gacts[-1]).mul_(2.0 / self.w.B)
         for l in reversed(range(len(self.w.layers))):
             s, p = self.w.layers[l], self.P[l]
-            self.binding.kan_backward(s, self.acts[l], p["coef"], p["w_s"], p["w_b"], self.gacts[l + 1],
-                                      out=self.outs[l], ws=self.ws_b[l])
+            self.binding.kan_backward_saved(s, self.acts[l], p["coef"], p["w_s"], p["w_b"], self.gacts[l + 1], self.ws_f[l],
+                                            out=self.outs[l], ws=self.ws_b[l])
 
     def step(self):
         self.forward()

@@ -119,6 +119,17 @@ int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const fl
                  const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
                  float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream);
 
+/* kan_backward for a training step that has just run kan_forward on the same layer: forward_ws is the
+   workspace that kan_forward call was given (it holds the scale-folded table, the first
+   kan_workspace_bytes(desc, B, KAN_PASS_FORWARD) bytes), untouched since, with coef, w_s and w_b unchanged;
+   the backward pass then reads the table from there instead of folding it again.  forward_ws must not be
+   the same buffer as ws (KAN_ERR_INVALID_ARG); NULL or misaligned gives KAN_ERR_WORKSPACE.  The library
+   cannot check that the table is current.  Results are bit-identical to kan_backward. */
+int kan_backward_saved(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                       const float *w_s, const float *w_b, const float *gy, const void *forward_ws,
+                       float *gx, float *gcoef, float *gw_s, float *gw_b, void *ws, size_t ws_bytes,
+                       void *stream);
+
 /* kan_forward for callers that cannot allocate device memory (code running under HIP graph capture, tight
    serving loops, harnesses that forbid hipMalloc): same arguments and result as kan_forward, but the scratch
    space is a fixed array of KAN_STATIC_SCRATCH_BYTES that is part of the library's device code, so there is

@@ -1,8 +1,9 @@
 """torch.autograd glue around the C-ABI entry points.
 
 Nothing is computed here: `forward` calls kan_forward / ukan_cg_forward_saved, `backward` calls
-kan_backward / ukan_cg_backward_saved with exactly the gradients autograd asks for (the UKAN
-backward pass reuses the coefficient table and the CG activations its forward pass kept).  Lets a stack of
+kan_backward_saved / ukan_cg_backward_saved with exactly the gradients autograd asks for (the
+backward passes reuse what their forward passes kept: the scale-folded table; for UKAN the
+coefficient table and the CG activations).  Lets a stack of
 layers be trained with a stock PyTorch optimizer (closed-form regression targets of the paper's
 experiments section need nothing else).
 """
@@ -17,18 +18,21 @@ class _KanLayer(torch.autograd.Function):
     @staticmethod
     def forward(ctx, spec, x, coef, w_s, w_b):
         ctx.spec = spec
-        ctx.save_for_backward(x, coef, w_s, w_b)
+        # the forward pass's workspace (the scale-folded table) is handed to the backward pass
+        ws = torch.empty(max(binding.kan_workspace_bytes(spec, x.shape[0], binding.PASS_FORWARD), 256), dtype=torch.uint8,
+                         device=x.device)
+        ctx.save_for_backward(x, coef, w_s, w_b, ws)
         return binding.kan_forward(spec, x.contiguous(), coef.contiguous(), w_s.contiguous(),
-                                   None if w_b is None else w_b.contiguous())
+                                   None if w_b is None else w_b.contiguous(), ws=ws)
 
     @staticmethod
     def backward(ctx, gy):
-        x, coef, w_s, w_b = ctx.saved_tensors
+        x, coef, w_s, w_b, ws = ctx.saved_tensors
         names = ("gx", "gcoef", "gw_s", "gw_b")
         need = ctx.needs_input_grad[1:5]
         want = tuple(n for n, k in zip(names, need) if k and not (n == "gw_b" and w_b is None))
-        g = binding.kan_backward(ctx.spec, x.contiguous(), coef.contiguous(), w_s.contiguous(),
-                                 None if w_b is None else w_b.contiguous(), gy.contiguous(), want=want) if want else {}
+        g = binding.kan_backward_saved(ctx.spec, x.contiguous(), coef.contiguous(), w_s.contiguous(),
+                                       None if w_b is None else w_b.contiguous(), gy.contiguous(), ws, want=want) if want else {}
         return (None,) + tuple(g.get(n) for n in names)
 
 

@@ -22,7 +22,7 @@ KAN_ERR_RANGE = -4
 KAN_ERR_HIP = -5
 PASS_FORWARD, PASS_BACKWARD = 0, 1
 
-EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_interval_index",
+EXPORTS = ["kan_strerror", "kan_workspace_bytes", "kan_forward", "kan_backward", "kan_backward_saved", "kan_interval_index",
            "kan_static_scratch_bytes", "kan_forward_static", "kan_set_launch_observer",
            "ukan_workspace_bytes", "ukan_cg_forward", "ukan_cg_backward", "ukan_saved_bytes",
            "ukan_cg_forward_saved", "ukan_cg_forward_saved_async", "ukan_cg_backward_saved", "ukan_materialize_workspace_bytes",
@@ -89,6 +89,8 @@ def load():
     lib.kan_forward_static.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp]
     lib.kan_backward.restype = ctypes.c_int
     lib.kan_backward.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kan_backward_saved.restype = ctypes.c_int
+    lib.kan_backward_saved.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kan_interval_index.restype = ctypes.c_int
     lib.kan_interval_index.argtypes = [ctypes.POINTER(KanLayerDesc), i64, vp, vp, vp]
     lib.kan_set_launch_observer.restype = ctypes.c_int
@@ -237,7 +239,9 @@ def kan_forward_static(spec, x, coef, w_s, w_b, y, stream=None):
 
 
 def kan_backward(spec, x, coef, w_s, w_b, gy, want=("gx", "gcoef", "gw_s", "gw_b"), out=None, ws=None,
-                 stream=None):
+                 stream=None, forward_ws=None):
+    """All (or the wanted) gradients of one layer.  forward_ws: the workspace tensor a kan_forward call on the same
+    layer and parameters used (kan_backward_saved: the scale-folded table is read from it, not rebuilt)."""
     lib = load()
     d = kan_desc(spec)
     B = x.shape[0]
@@ -249,12 +253,22 @@ def kan_backward(spec, x, coef, w_s, w_b, gy, want=("gx", "gcoef", "gw_s", "gw_b
             out[name] = _on_stream(torch.empty(shapes[name], dtype=torch.float32, device=x.device), stream)
     if ws is None:
         ws = _workspace(lib.kan_workspace_bytes(ctypes.byref(d), B, PASS_BACKWARD), x.device, stream)
-    rc = lib.kan_backward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
-                          _f32(out.get("gx")), _f32(out.get("gcoef")), _f32(out.get("gw_s")),
-                          _f32(out.get("gw_b")), _ptr(ws), ws.numel(), _stream(stream))
+    if forward_ws is not None:
+        rc = lib.kan_backward_saved(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
+                                    _ptr(forward_ws), _f32(out.get("gx")), _f32(out.get("gcoef")), _f32(out.get("gw_s")),
+                                    _f32(out.get("gw_b")), _ptr(ws), ws.numel(), _stream(stream))
+    else:
+        rc = lib.kan_backward(ctypes.byref(d), B, _f32(x), _f32(coef), _f32(w_s), _f32(w_b), _f32(gy),
+                              _f32(out.get("gx")), _f32(out.get("gcoef")), _f32(out.get("gw_s")),
+                              _f32(out.get("gw_b")), _ptr(ws), ws.numel(), _stream(stream))
     if rc != KAN_OK:
-        raise KanError(rc, "kan_backward")
+        raise KanError(rc, "kan_backward_saved" if forward_ws is not None else "kan_backward")
     return out
+
+
+def kan_backward_saved(spec, x, coef, w_s, w_b, gy, forward_ws, want=("gx", "gcoef", "gw_s", "gw_b"), out=None, ws=None,
+                       stream=None):
+    return kan_backward(spec, x, coef, w_s, w_b, gy, want=want, out=out, ws=ws, stream=stream, forward_ws=forward_ws)
 
 
 def kan_interval_index(spec, x, stream=None):

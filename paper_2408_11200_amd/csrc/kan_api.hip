@@ -215,9 +215,10 @@ extern "C" int kan_forward_static(const kan_layer_desc *desc, int64_t B, const f
     return forward_impl(desc, B, x, coef, w_s, w_b, y, ws, KAN_STATIC_SCRATCH_BYTES, stream);
 }
 
-extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
-                            const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
-                            float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream)
+// Backward pass; `folded` (may be null) is the scale-folded table a forward pass left in its workspace.
+static int backward_impl(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                         const float *w_s, const float *w_b, const float *gy, const float *folded, float *gx,
+                         float *gcoef, float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream)
 {
     int rc = check_desc(desc);
     if (rc != KAN_OK) return rc;
@@ -234,6 +235,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     SplineGeom g = geom_of(desc);
     float *cf = (float *)ws;
     const BackwardPlan bp = backward_plan(desc, B);
+    if (misaligned(folded)) return KAN_ERR_INVALID_ARG;
     if (high_degree(desc) && !bp.walk) {
         float *part_c = (float *)((char *)ws + folded_bytes(desc));
         float *part_b = (float *)((char *)part_c + (size_t)bp.n_slabs * folded_bytes(desc));
@@ -245,11 +247,14 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
     const bool want_params = gcoef || gw_s || gw_b;
     // the chunk-sorted walk takes dL/dx together with the parameter gradients (one pass over gy)
     const bool fused_dx = gx && bp.walk;
+    const float *table = folded ? folded : cf;        // the table dL/dx reads
     if (gx) {
-        if (launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess) return KAN_ERR_HIP;
+        if (!folded &&
+            launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st) != hipSuccess)
+            return KAN_ERR_HIP;
         if (!fused_dx) {
-            hipError_t e = narrow_applicable(g) ? launch_dx_narrow(g, x, cf, w_b, gy, gx, B, st)
-                                                : launch_dx_generic(g, x, cf, w_b, gy, gx, B, st);
+            hipError_t e = narrow_applicable(g) ? launch_dx_narrow(g, x, table, w_b, gy, gx, B, st)
+                                                : launch_dx_generic(g, x, table, w_b, gy, gx, B, st);
             if (e != hipSuccess) return KAN_ERR_HIP;
         }
     }
@@ -262,7 +267,7 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
         float *part_c = (float *)at;
         float *part_b = (float *)((char *)part_c + (size_t)bp.n_slabs * folded_bytes(desc) + bp.tail_bytes);
         // partial slabs are laid out back to back with the unpadded slab size
-        hipError_t e = bp.walk ? launch_backward_walk(g, bp.wp, x, gy, cf, w_b, walk_scratch, fused_dx ? gx : nullptr,
+        hipError_t e = bp.walk ? launch_backward_walk(g, bp.wp, x, gy, table, w_b, walk_scratch, fused_dx ? gx : nullptr,
                                                       want_params ? part_c : nullptr, want_b ? part_b : nullptr, B, st)
                                : launch_dparam_generic(g, x, gy, part_c, want_b ? part_b : nullptr, B, cp.n_chunks,
                                                        cp.chunk_len, st);
@@ -275,6 +280,24 @@ extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *
             return KAN_ERR_HIP;
     }
     return KAN_OK;
+}
+
+extern "C" int kan_backward(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                            const float *w_s, const float *w_b, const float *gy, float *gx, float *gcoef,
+                            float *gw_s, float *gw_b, void *ws, size_t ws_bytes, void *stream)
+{
+    return backward_impl(desc, B, x, coef, w_s, w_b, gy, nullptr, gx, gcoef, gw_s, gw_b, ws, ws_bytes, stream);
+}
+
+extern "C" int kan_backward_saved(const kan_layer_desc *desc, int64_t B, const float *x, const float *coef,
+                                  const float *w_s, const float *w_b, const float *gy, const void *forward_ws,
+                                  float *gx, float *gcoef, float *gw_s, float *gw_b, void *ws, size_t ws_bytes,
+                                  void *stream)
+{
+    if (!forward_ws || ((uintptr_t)forward_ws % kAlign) != 0) return KAN_ERR_WORKSPACE;
+    if (forward_ws == ws) return KAN_ERR_INVALID_ARG;          // the backward scratch would overwrite the table
+    return backward_impl(desc, B, x, coef, w_s, w_b, gy, (const float *)forward_ws, gx, gcoef, gw_s, gw_b, ws,
+                         ws_bytes, stream);
 }
 
 extern "C" int kan_interval_index(const kan_layer_desc *desc, int64_t n, const float *x, int32_t *idx,

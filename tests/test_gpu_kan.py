@@ -364,6 +364,25 @@ def test_step_captured_in_a_graph_replays_to_the_eager_result():
     assert not torch.equal(ref2[0], ref[0])
 
 
+@pytest.mark.parametrize("B,n_in,n_out,G,k", [(3000, 24, 128, 12, 3), (500, 5, 8, 30, 3), (900, 6, 33, 9, 2), (700, 4, 64, 10, 5)])
+def test_backward_on_the_forward_pass_table(B, n_in, n_out, G, k):
+    """kan_backward_saved reads the scale-folded table the forward pass left in its workspace: bit for bit the
+    gradients of kan_backward (walk, narrow, generic and degree-5 paths)."""
+    w = workloads.random_kan_layer(61 + B, B, n_in, n_out, G, k, outside_frac=0.1)
+    s, p = w.layers[0], w.params[0]
+    x, coef, w_s, w_b, gy = (dev(a) for a in (w.x, p["coef"], p["w_s"], p["w_b"], w.gy))
+    ws_f = torch.empty(max(binding.kan_workspace_bytes(s, B, binding.PASS_FORWARD), 256), dtype=torch.uint8, device="cuda")
+    binding.kan_forward(s, x, coef, w_s, w_b, ws=ws_f)
+    ref = binding.kan_backward(s, x, coef, w_s, w_b, gy)
+    got = binding.kan_backward_saved(s, x, coef, w_s, w_b, gy, ws_f)
+    for n in ref:
+        assert torch.equal(got[n], ref[n]), n
+    ws_b = torch.empty(binding.kan_workspace_bytes(s, B, binding.PASS_BACKWARD), dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.KanError) as e:
+        binding.kan_backward_saved(s, x, coef, w_s, w_b, gy, ws_b, ws=ws_b)
+    assert e.value.status == binding.KAN_ERR_INVALID_ARG
+
+
 def test_config2_full_size():
     """64->64, G=10, batch 65536 with 5% of the samples outside the grid: every output element."""
     run_layer_parity(workloads.config2())

@@ -49,7 +49,7 @@ extern "C" {
 typedef enum kan_status {
     KAN_OK = 0,
     KAN_ERR_INVALID_ARG = -1, /* null or misaligned pointer, non-positive size, grid_hi <= grid_lo, h <= 0 */
-    KAN_ERR_UNSUPPORTED = -2, /* k outside 1..5 (UKAN: 1..3), n_in above 65535, unknown base_act, odd d_pe */
+    KAN_ERR_UNSUPPORTED = -2, /* k outside 1..5, n_in above 65535, unknown base_act, odd d_pe */
     KAN_ERR_WORKSPACE = -3,   /* ws is NULL / misaligned / smaller than *_workspace_bytes     */
     KAN_ERR_RANGE = -4,       /* UKAN: some input spans more groups than max_groups           */
     KAN_ERR_HIP = -5          /* a HIP runtime call or kernel launch failed                   */
@@ -67,7 +67,7 @@ typedef struct kan_layer_desc {
     int32_t base_act;
 } kan_layer_desc;
 
-/* One UKAN layer (section "Algorithm", CG paragraph): unbounded grid t_j = j*h, degree k,
+/* One UKAN layer (section "Algorithm", CG paragraph): unbounded grid t_j = j*h, degree k (1..5),
    groups of K = k+1 cells; CG input = [feature embedding (d_feat) ; sinusoidal PE of the group
    index (d_pe)], one hidden layer of d_hidden units with SiLU, K*n_out outputs.           */
 typedef struct ukan_layer_desc {

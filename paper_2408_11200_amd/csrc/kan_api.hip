@@ -59,7 +59,7 @@ bool high_degree(const kan_layer_desc *d) { return d->k > 3; }
 
 HighKLayer highk_of(const kan_layer_desc *d)
 {
-    HighKLayer l;
+    HighKLayer l = {};
     l.n_in = d->n_in; l.n_out = d->n_out; l.rows = d->G + d->k; l.k = d->k;
     l.lo = d->grid_lo; l.inv_h = (float)d->G / (d->grid_hi - d->grid_lo);
     l.base_act = d->base_act;

@@ -13,11 +13,29 @@ namespace {
 kan_k5::SplineGeom geom_of(const HighKLayer &l)
 {
     kan_k5::SplineGeom g;
-    g.n_in = l.n_in; g.n_out = l.n_out; g.rows = l.rows; g.slab_rows = l.rows + 1; g.k = l.k;
-    g.lo = l.lo; g.inv_h = l.inv_h; g.cell_base = nullptr; g.base_act = l.base_act;
+    g.n_in = l.n_in; g.n_out = l.n_out; g.rows = l.rows; g.slab_rows = l.slab_rows ? l.slab_rows : l.rows + 1; g.k = l.k;
+    g.lo = l.lo; g.inv_h = l.inv_h; g.cell_base = l.cell_base; g.base_act = l.base_act;
     return g;
 }
 }  // namespace
+
+hipError_t highk_table_forward(const HighKLayer &l, const float *x, const float *table, const float *w_b, float *y,
+                               int64_t B, hipStream_t st)
+{
+    return kan_k5::launch_forward_generic(geom_of(l), x, table, w_b, y, B, st);
+}
+
+hipError_t highk_table_dx(const HighKLayer &l, const float *x, const float *table, const float *w_b, const float *gy,
+                          float *gx, int64_t B, hipStream_t st)
+{
+    return kan_k5::launch_dx_generic(geom_of(l), x, table, w_b, gy, gx, B, st);
+}
+
+hipError_t highk_table_dparam(const HighKLayer &l, const float *x, const float *gy, float *part_c, float *part_b,
+                              int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st)
+{
+    return kan_k5::launch_dparam_generic(geom_of(l), x, gy, part_c, part_b, B, n_chunks, chunk_len, st);
+}
 
 int highk_row_blocks(int rows) { return kan_k5::dparam_generic_row_blocks(rows); }
 

@@ -10,6 +10,10 @@ struct HighKLayer {
     int n_in, n_out, rows, k;       // rows = G + k
     float lo, inv_h;
     int base_act;
+    // optional (zero-initialise the struct): a table of slab_rows rows per input (0: rows + 1, the last one w_b) whose
+    // first row is cell cell_base[i] of input i (device pointer; null: cell 0)
+    int slab_rows;
+    const int *cell_base;
 };
 
 int highk_row_blocks(int rows);     // base-term partial slices per chunk
@@ -21,6 +25,16 @@ hipError_t highk_forward(const HighKLayer &l, const float *x, const float *coef,
 hipError_t highk_backward(const HighKLayer &l, const float *x, const float *coef, const float *w_s, const float *w_b,
                           const float *gy, float *cf, float *gx, float *gcoef, float *gw_s, float *gw_b,
                           float *part_c, float *part_b, int n_chunks, int64_t chunk_len, int64_t B, hipStream_t st);
+
+// The generic kernels on an existing table (UKAN layers of degree 4 and 5): forward, dL/dx, and the per-chunk
+// partial sums of the table gradient (part_c: n_chunks tables of rows rows, part_b: n_chunks * highk_row_blocks(rows)
+// edge slices or null).  w_b may be null.
+hipError_t highk_table_forward(const HighKLayer &l, const float *x, const float *table, const float *w_b, float *y,
+                               int64_t B, hipStream_t st);
+hipError_t highk_table_dx(const HighKLayer &l, const float *x, const float *table, const float *w_b, const float *gy,
+                          float *gx, int64_t B, hipStream_t st);
+hipError_t highk_table_dparam(const HighKLayer &l, const float *x, const float *gy, float *part_c, float *part_b,
+                              int64_t B, int n_chunks, int64_t chunk_len, hipStream_t st);
 
 // Sorted records of the walk for degrees 4 and 5 (kan_walk_k5.hip): per (chunk of S samples, input) a list of
 // 2 S records in the four-row format of the walk, two per pair (rows 0..3 of its six-row window with the base

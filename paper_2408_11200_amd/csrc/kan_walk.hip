@@ -388,8 +388,9 @@ hipError_t launch_backward_walk(const SplineGeom &g, const WalkPlan &p, const fl
             prof::Timed tm("walk_transpose", st);
             transpose_kernel<<<grid, 256, 0, st>>>(x, xT, B, g.n_in);
         }
-        HighKLayer l;
+        HighKLayer l = {};
         l.n_in = g.n_in; l.n_out = g.n_out; l.rows = g.rows; l.k = g.k; l.lo = g.lo; l.inv_h = g.inv_h; l.base_act = g.base_act;
+        l.slab_rows = g.slab_rows; l.cell_base = g.cell_base;
         if (hipError_t e = highk_sorted_records(l, xT, B, p.S, p.row_bits, rec.rt, rec.base, rec.w4, rec.dbase, rec.dw4, st);
             e != hipSuccess)
             return e;

@@ -197,8 +197,8 @@ hipError_t highk_sorted_records(const HighKLayer &l, const float *xT, int64_t B,
 {
     if (S < 256 || S > 4096 || (S & (S - 1)) != 0 || l.rows < 6) return hipErrorInvalidValue;
     kan_k5::SplineGeom g;
-    g.n_in = l.n_in; g.n_out = l.n_out; g.rows = l.rows; g.slab_rows = l.rows + 1; g.k = l.k;
-    g.lo = l.lo; g.inv_h = l.inv_h; g.cell_base = nullptr; g.base_act = l.base_act;
+    g.n_in = l.n_in; g.n_out = l.n_out; g.rows = l.rows; g.slab_rows = l.slab_rows ? l.slab_rows : l.rows + 1; g.k = l.k;
+    g.lo = l.lo; g.inv_h = l.inv_h; g.cell_base = l.cell_base; g.base_act = l.base_act;
     int sbits = 0;
     while ((1 << sbits) < S) ++sbits;
     const size_t lds = (size_t)S * 20;              // two key arrays of 2 S entries and the S sample values

@@ -4,6 +4,7 @@
 #include <initializer_list>
 #include "kan.h"
 #include "kan_launch.hpp"
+#include "kan_highk.hpp"
 #include "ukan_launch.hpp"
 
 using namespace kan;
@@ -18,7 +19,7 @@ int check_desc(const ukan_layer_desc *d)
     if (!d) return KAN_ERR_INVALID_ARG;
     if (d->n_in <= 0 || d->n_out <= 0 || !(d->h > 0.0f)) return KAN_ERR_INVALID_ARG;
     if (d->d_pe <= 0 || d->d_feat < 0 || d->d_hidden <= 0) return KAN_ERR_INVALID_ARG;
-    if (d->k < 1 || d->k > 3) return KAN_ERR_UNSUPPORTED;
+    if (d->k < 1 || d->k > 5) return KAN_ERR_UNSUPPORTED;
     if (d->n_in > 65535) return KAN_ERR_UNSUPPORTED;          // inputs index a 16-bit launch dimension
     if (d->d_pe % 2 != 0) return KAN_ERR_UNSUPPORTED;         // sin/cos pairs
     if (d->base_act != KAN_BASE_NONE && d->base_act != KAN_BASE_SILU) return KAN_ERR_UNSUPPORTED;
@@ -31,14 +32,30 @@ WalkPlan walk_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
     SplineGeom g = {};
     g.n_in = d->n_in; g.n_out = d->n_out; g.rows = max_groups * (d->k + 1); g.slab_rows = g.rows; g.k = d->k;
-    return plan_walk(g, B);
+    return plan_walk(g, B, false, d->k > 3);     // degrees 4 and 5: two four-row records per pair
+}
+
+// degrees 4 and 5 run the kernels built for a window of six rows
+bool high_degree(const ukan_layer_desc *d) { return d->k > 3; }
+
+HighKLayer highk_of(const SplineGeom &g)
+{
+    HighKLayer l = {};
+    l.n_in = g.n_in; l.n_out = g.n_out; l.rows = g.rows; l.k = g.k; l.lo = g.lo; l.inv_h = g.inv_h;
+    l.base_act = g.base_act; l.slab_rows = g.slab_rows; l.cell_base = g.cell_base;
+    return l;
+}
+
+int row_blocks_for(const ukan_layer_desc *d, int rows)
+{
+    return high_degree(d) ? highk_row_blocks(rows) : dparam_generic_row_blocks(rows);
 }
 
 // base-term partial slices each chunk writes
 int b_slices_for(const ukan_layer_desc *d, int64_t B, int32_t max_groups)
 {
     const WalkPlan wp = walk_for(d, B, max_groups);
-    return wp.ok ? wp.n_seg : dparam_generic_row_blocks(max_groups * (d->k + 1));
+    return wp.ok ? wp.n_seg : row_blocks_for(d, max_groups * (d->k + 1));
 }
 
 // scratch of the walk's pre-pass (transposed x + sorted records)
@@ -246,7 +263,8 @@ int forward_impl(const ukan_layer_desc *desc, int64_t B, const float *x, const u
     rc = prepare(desc, B, x, p, max_groups, (char *)ws, KAN_PASS_FORWARD, st, &pr, saved, provided_span, overflow);
     if (rc != KAN_OK) return rc;
     if (span) *span = pr.n_g;
-    hipError_t e = narrow_applicable(pr.g)            ? launch_forward_narrow(pr.g, x, pr.cf, p->w_b, y, B, st)
+    hipError_t e = high_degree(desc)                  ? highk_table_forward(highk_of(pr.g), x, pr.cf, p->w_b, y, B, st)
+                   : narrow_applicable(pr.g)        ? launch_forward_narrow(pr.g, x, pr.cf, p->w_b, y, B, st)
                    : forward_lds_rows_plan(pr.g, B) ? launch_forward_lds_rows(pr.g, x, pr.cf, y, B, st)
                                                     : launch_forward_generic(pr.g, x, pr.cf, p->w_b, y, B, st);
     if (e != hipSuccess) return KAN_ERR_HIP;
@@ -358,8 +376,9 @@ int backward_body(const ukan_layer_desc *desc, int64_t B, const float *x, const 
     const WalkPlan wp = walk_for(desc, B, max_groups);
     const bool fused_dx = gx && wp.ok;      // dL/dx rides along with the table gradient
     if (gx && !fused_dx) {
-        hipError_t e = narrow ? launch_dx_narrow(pr.g, x, pr.cf, p->w_b, gy, gx, B, st)
-                              : launch_dx_generic(pr.g, x, pr.cf, p->w_b, gy, gx, B, st);
+        hipError_t e = high_degree(desc) ? highk_table_dx(highk_of(pr.g), x, pr.cf, p->w_b, gy, gx, B, st)
+                       : narrow          ? launch_dx_narrow(pr.g, x, pr.cf, p->w_b, gy, gx, B, st)
+                                         : launch_dx_generic(pr.g, x, pr.cf, p->w_b, gy, gx, B, st);
         if (e != hipSuccess) return KAN_ERR_HIP;
     }
 
@@ -378,10 +397,13 @@ int backward_body(const ukan_layer_desc *desc, int64_t B, const float *x, const 
             return KAN_ERR_HIP;
         b_slices = pr.cp.n_chunks * wp.n_seg;
     } else {
-        if (launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,
-                                  pr.cp.chunk_len, st) != hipSuccess)
-            return KAN_ERR_HIP;
-        b_slices = pr.cp.n_chunks * dparam_generic_row_blocks(pr.g.rows);
+        hipError_t e = high_degree(desc)
+                           ? highk_table_dparam(highk_of(pr.g), x, gy, part_c, want_b ? part_b : nullptr, B,
+                                                pr.cp.n_chunks, pr.cp.chunk_len, st)
+                           : launch_dparam_generic(pr.g, x, gy, part_c, want_b ? part_b : nullptr, B, pr.cp.n_chunks,
+                                                   pr.cp.chunk_len, st);
+        if (e != hipSuccess) return KAN_ERR_HIP;
+        b_slices = pr.cp.n_chunks * row_blocks_for(desc, pr.g.rows);
     }
     if (!want_params) return KAN_OK;
     if (launch_dparam_reduce(part_c, want_b ? part_b : nullptr, pr.raw, p->scale,

@@ -74,6 +74,29 @@ def test_ukan_layer_parity_sweep(B, n_in, n_out, k, base_act):
     run(spec, p, x, gy)
 
 
+@pytest.mark.parametrize("B,n_in,n_out,k,base_act", [
+    (300, 5, 64, 4, 1),        # walk with two records per pair, four streams per wave
+    (513, 16, 256, 5, 0),      # one stream per wave
+    (2000, 6, 20, 5, 1),       # two outputs per lane
+    (50, 3, 4, 4, 1),          # narrow layer
+    (257, 9, 130, 5, 1),       # a width the walk does not cover: six-row generic kernels on the table
+    (9000, 4, 32, 4, 0),       # three chunks of 4096 samples (the two-record mode's limit), ragged last one
+])
+def test_ukan_degrees_four_and_five(B, n_in, n_out, k, base_act):
+    """UKAN layers of degree 4 and 5: groups of K = 5 and 6 cells, six-row kernels on the generated table, and
+    the saved hand-off on top."""
+    spec, p, x, gy = make(40 + B, B, n_in, n_out, k=k, base_act=base_act)
+    gy = np.float32(gy / np.sqrt(B))
+    run(spec, p, x, gy, max_groups=64)
+    pd = {n: dev(a) for n, a in p.items()}
+    xd, gyd = dev(x), dev(gy)
+    g_ref = binding.ukan_cg_backward(spec, xd, pd, gyd, 64)
+    y, saved, span = binding.ukan_cg_forward_saved(spec, xd, pd, 64)
+    g = binding.ukan_cg_backward_saved(spec, xd, pd, gyd, 64, saved, span)
+    for n in g:
+        assert torch.equal(g[n], g_ref[n]), n
+
+
 def _random_ukan_shapes(n, seed):
     rng = np.random.default_rng(seed)
     return [(int(rng.integers(1, 1500)), int(rng.integers(1, 20)), int(rng.choice([1, 5, 8, 32, 64, 100, 256, 260])),
@@ -113,19 +136,20 @@ def test_ukan_equals_kan_on_materialised_table():
     assert_close(y_ukan, ref, 2e-5, "ukan vs kan")
 
 
-def test_ukan_materialize_matches_oracle_and_ukan_forward():
+@pytest.mark.parametrize("k", [3, 5])
+def test_ukan_materialize_matches_oracle_and_ukan_forward(k):
     """The exported table equals the oracle's, also for negative cells and a range that starts inside a
     group; kan_forward on it reproduces ukan_cg_forward."""
-    spec, p, x, gy = make(9, 600, 5, 32, xs=2.5)
+    spec, p, x, gy = make(9, 600, 5, 32, k=k, xs=2.5)
     P = {n: dev(a) for n, a in p.items()}
     for c_lo, c_hi in [(-13, 9), (2, 2), (-3, -1), (0, 40)]:
         got = binding.ukan_materialize(spec, P, c_lo, c_hi)
-        assert_close(got, oracle.ukan_materialize(p, 3, c_lo, c_hi), 1e-5, "table %d..%d" % (c_lo, c_hi))
+        assert_close(got, oracle.ukan_materialize(p, k, c_lo, c_hi), 1e-5, "table %d..%d" % (c_lo, c_hi))
     inv_h = oracle.inv_h_of_spacing(spec.h)
-    cell, _, _ = oracle.group_index(x, inv_h, 4)
+    cell, _, _ = oracle.group_index(x, inv_h, k + 1)
     c_lo, c_hi = int(cell.min()), int(cell.max())
     coef = binding.ukan_materialize(spec, P, c_lo, c_hi)
-    kspec = workloads.KanLayerSpec(5, 32, c_hi - c_lo + 1, 3, c_lo * spec.h, (c_hi + 1) * spec.h, base_act=0)
+    kspec = workloads.KanLayerSpec(5, 32, c_hi - c_lo + 1, k, c_lo * spec.h, (c_hi + 1) * spec.h, base_act=0)
     y_kan = binding.kan_forward(kspec, dev(x), coef, torch.ones((5, 32), device="cuda"), None)
     y_ukan = binding.ukan_cg_forward(spec, dev(x), P, 64)
     assert_close(y_ukan, y_kan.double().cpu().numpy(), 2e-5, "ukan vs kan on the exported table")
@@ -148,7 +172,7 @@ def test_ukan_range_error_and_arguments():
     lib = binding.load()
     d = binding.ukan_desc(spec)
     assert lib.ukan_workspace_bytes(ctypes.byref(d), 64, 1, 0) == 0
-    d.k = 5
+    d.k = 6
     assert lib.ukan_workspace_bytes(ctypes.byref(d), 64, 16, 0) == 0
     y = binding.ukan_cg_forward(spec, torch.empty((0, 3), device="cuda"), pd, 16)
     assert y.shape == (0, 8)

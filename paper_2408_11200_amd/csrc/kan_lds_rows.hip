@@ -191,6 +191,10 @@ RowsPlan plan_of(const SplineGeom &g, int64_t B)
             const int64_t per_wg = (int64_t)nw * spw * kSlots;
             const int64_t wgs = (B + per_wg - 1) / per_wg * tiles;
             if (nw == 16 && wgs < 256) continue;
+            // eight waves (two per SIMD) only when one tile covers the layer: with several tiles every tile
+            // evaluates the pairs again and the smaller workgroup did not beat the generic kernel (256 -> 256,
+            // G = 200, B = 8192: 0.38 ms against 0.34 ms)
+            if (nw == 8 && tiles > 1) continue;
             const int64_t quads = (int64_t)g.slab_rows * lps;
             const int64_t need = (quads + 64 * nw - 1) / (64 * nw);
             const int sizes[] = {2, 4, 8, 16};

@@ -46,6 +46,7 @@ hipError_t highk_forward(const HighKLayer &l, const float *x, const float *coef,
     hipError_t e = kan_k5::launch_fold_scale(coef, w_s, g.base_act ? w_b : nullptr, cf, g.n_in, g.rows, g.n_out, st);
     if (e != hipSuccess) return e;
     if (kan_k5::forward_rows_plan(g)) return kan_k5::launch_forward_rows(g, x, cf, y, B, st);
+    if (kan_k5::forward_lds_plan(g)) return kan_k5::launch_forward_lds(g, x, cf, y, B, st);
     return kan_k5::launch_forward_generic(g, x, cf, w_b, y, B, st);
 }
 

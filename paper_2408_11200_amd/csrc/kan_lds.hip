@@ -11,7 +11,7 @@
 #include "kan_device.hpp"
 #include "kan_launch.hpp"
 
-namespace kan {
+namespace KAN_NS {
 
 namespace {
 
@@ -224,7 +224,10 @@ __global__ __launch_bounds__(64 * NW) void forward_pairs_kernel(SplineGeom g, co
 {
     constexpr int TJ = 64 * R, NT = 64 * NW, IPV = kWave / T;
     constexpr int slab_floats = NQ * NT * 4;            // padded slab
-    constexpr int kPairFloats = 8;                      // w[0..3], base, byte offset of the window row, 2 unused
+    // one pair: the window weights, the base value and the byte offset of the window row, as two quadruples:
+    // window of four rows  {w0 w1 w2 w3} {base offset - -},  window of six rows  {w0 w1 w2 w3} {w4 w5 base offset}
+    constexpr int kPairFloats = 8;
+    static_assert(kMaxK == 4 || kMaxK == 6, "pair records are laid out for windows of four and six rows");
     extern __shared__ float lds[];                      // two slabs, then NW areas of 64 pairs
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t b0 = ((int64_t)blockIdx.x * NW + wave) * T;
@@ -254,8 +257,12 @@ __global__ __launch_bounds__(64 * NW) void forward_pairs_kernel(SplineGeom g, co
         const WinPair p = window_pair<false>(x[my_b * g.n_in + ic], g, ic);
         // pair (input i0 + ii, sample t) sits at index ii * T + t == lane of the lane that evaluated it
         *reinterpret_cast<float4 *>(pairs + lane * kPairFloats) = make_float4(p.w[0], p.w[1], p.w[2], p.w[3]);
-        *reinterpret_cast<float2 *>(pairs + lane * kPairFloats + 4) =
-            make_float2(p.base, __int_as_float(p.row0 * TJ * 4));
+        if constexpr (kMaxK == 4)
+            *reinterpret_cast<float2 *>(pairs + lane * kPairFloats + 4) =
+                make_float2(p.base, __int_as_float(p.row0 * TJ * 4));
+        else
+            *reinterpret_cast<float4 *>(pairs + lane * kPairFloats + 4) =
+                make_float4(p.w[kMaxK - 2], p.w[kMaxK - 1], p.base, __int_as_float(p.row0 * TJ * 4));
         const int n_ii = (g.n_in - i0 < IPV) ? g.n_in - i0 : IPV;
         for (int ii = 0; ii < n_ii; ++ii) {
             const int i = i0 + ii;
@@ -265,31 +272,37 @@ __global__ __launch_bounds__(64 * NW) void forward_pairs_kernel(SplineGeom g, co
             slab_fetch<NQ>(q, map, cf + (int64_t)(i + 1 < g.n_in ? i + 1 : i) * block_floats);
 
             // the T pairs of this input: same address in every lane
-            float4 wv[T];
-            float2 bv[T];
+            float ws[T][kMaxK], bs[T];
+            int off[T];
             const float *pp = pairs + ii * (T * kPairFloats);
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                wv[t] = *reinterpret_cast<const float4 *>(pp + t * kPairFloats);
-                bv[t] = *reinterpret_cast<const float2 *>(pp + t * kPairFloats + 4);
+                const float4 wv = *reinterpret_cast<const float4 *>(pp + t * kPairFloats);
+                ws[t][0] = wv.x; ws[t][1] = wv.y; ws[t][2] = wv.z; ws[t][3] = wv.w;
+                if constexpr (kMaxK == 4) {
+                    const float2 bv = *reinterpret_cast<const float2 *>(pp + t * kPairFloats + 4);
+                    bs[t] = bv.x; off[t] = __float_as_int(bv.y);
+                } else {
+                    const float4 bv = *reinterpret_cast<const float4 *>(pp + t * kPairFloats + 4);
+                    ws[t][kMaxK - 2] = bv.x; ws[t][kMaxK - 1] = bv.y;
+                    bs[t] = bv.z; off[t] = __float_as_int(bv.w);
+                }
             }
             float wb[R];
             lds_row<R>(cur + g.rows * TJ, lane, wb);   // last slab row: w_b
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                const float *win = reinterpret_cast<const float *>(reinterpret_cast<const char *>(cur) +
-                                                                   __float_as_int(bv[t].y));
+                const float *win = reinterpret_cast<const float *>(reinterpret_cast<const char *>(cur) + off[t]);
                 float c[kMaxK][R];
 #pragma unroll
                 for (int s = 0; s < kMaxK; ++s) lds_row<R>(win + s * TJ, lane, c[s]);
-                const float ws[kMaxK] = {wv[t].x, wv[t].y, wv[t].z, wv[t].w};
 #pragma unroll
                 for (int s = 0; s < kMaxK; ++s)
 #pragma unroll
-                    for (int r = 0; r < R; ++r) acc[t][r] = fmaf(ws[s], c[s][r], acc[t][r]);
+                    for (int r = 0; r < R; ++r) acc[t][r] = fmaf(ws[t][s], c[s][r], acc[t][r]);
 #pragma unroll
-                for (int r = 0; r < R; ++r) acc[t][r] = fmaf(bv[t].x, wb[r], acc[t][r]);
+                for (int r = 0; r < R; ++r) acc[t][r] = fmaf(bs[t], wb[r], acc[t][r]);
                 __builtin_amdgcn_sched_barrier(0);
             }
             slab_store<NT, NQ, MASK>(q, map, nxt, tid);
@@ -415,4 +428,4 @@ hipError_t launch_forward_lds(const SplineGeom &g, const float *x, const float *
     }
 }
 
-}  // namespace kan
+}  // namespace KAN_NS

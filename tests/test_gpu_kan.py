@@ -93,6 +93,8 @@ def test_layer_parity_sweep(B, n_in, n_out, G, k, outside):
 
 @pytest.mark.parametrize("B,n_in,n_out,G,k,outside", [
     (300, 7, 96, 9, 4, 0.2), (513, 5, 33, 12, 5, 0.25), (64, 3, 256, 40, 5, 0.1), (1000, 4, 8, 6, 4, 0.3),
+    (96, 33, 512, 20, 5, 0.05), (200, 8, 256, 12, 4, 0.2), (300, 20, 128, 8, 5, 0.1),     # six-row LDS-staged forward
+    (130, 7, 260, 10, 4, 0.1),                                                           # ... with a ragged last tile
 ])
 def test_layer_parity_degrees_four_and_five(B, n_in, n_out, G, k, outside):
     """Degrees 4 and 5 (window of 5 and 6 rows)."""

@@ -350,15 +350,24 @@ hipError_t launch_sorted_records(const SplineGeom &g, const float *x, float *xT,
         transpose_kernel<<<grid, 256, 0, st>>>(x, xT, B, g.n_in);
     }
     const size_t lds = (size_t)S * 12;
-    // long chunks: 16 waves per sort (one workgroup per CU fits anyway), short ones 4
-    auto kern = S >= 4096 ? cell_sort_kernel<16> : cell_sort_kernel<4>;
-    struct Long; struct Short;
-    hipError_t e = S >= 4096 ? ensure_dynamic_lds<Long>(reinterpret_cast<const void *>(kern), (int)lds)
-                             : ensure_dynamic_lds<Short>(reinterpret_cast<const void *>(kern), (int)lds);
-    if (e != hipSuccess) return e;
+    // waves per sort, measured: 16 for chunks of 8192 samples, 8 for 4096, 4 below
     dim3 grid((unsigned)((B + S - 1) / S), (unsigned)g.n_in);
     prof::Timed tm("walk_sort", st);
-    kern<<<grid, S >= 4096 ? 1024 : 256, lds, st>>>(g, xT, B, S, log2_exact(S), row_bits, rec);
+    struct W16; struct W8; struct W4;
+    hipError_t e;
+    if (S >= 8192) {
+        auto kern = cell_sort_kernel<16>;
+        if ((e = ensure_dynamic_lds<W16>(reinterpret_cast<const void *>(kern), (int)lds)) != hipSuccess) return e;
+        kern<<<grid, 1024, lds, st>>>(g, xT, B, S, log2_exact(S), row_bits, rec);
+    } else if (S >= 4096) {
+        auto kern = cell_sort_kernel<8>;
+        if ((e = ensure_dynamic_lds<W8>(reinterpret_cast<const void *>(kern), (int)lds)) != hipSuccess) return e;
+        kern<<<grid, 512, lds, st>>>(g, xT, B, S, log2_exact(S), row_bits, rec);
+    } else {
+        auto kern = cell_sort_kernel<4>;
+        if ((e = ensure_dynamic_lds<W4>(reinterpret_cast<const void *>(kern), (int)lds)) != hipSuccess) return e;
+        kern<<<grid, 256, lds, st>>>(g, xT, B, S, log2_exact(S), row_bits, rec);
+    }
     return hipGetLastError();
 }
 

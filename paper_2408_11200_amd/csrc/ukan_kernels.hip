@@ -44,7 +44,21 @@ __global__ __launch_bounds__(256) void range_kernel(const float *__restrict__ x,
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_in) return;
     int lo = INT_MAX, hi = INT_MIN;
-    for (int64_t b = blockIdx.y; b < B; b += gridDim.y) {
+    int64_t b = blockIdx.y;
+    // four rows in flight per thread (the scan is bound by load latency otherwise)
+    for (; b + 3 * (int64_t)gridDim.y < B; b += 4 * (int64_t)gridDim.y) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = x[(b + u * (int64_t)gridDim.y) * n_in + i];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float t, d;
+            const int c = interval_index(v[u], 0.0f, inv_h, &t, &d);
+            lo = c < lo ? c : lo;
+            hi = c > hi ? c : hi;
+        }
+    }
+    for (; b < B; b += gridDim.y) {
         float t, d;
         int c = interval_index(x[b * n_in + i], 0.0f, inv_h, &t, &d);
         lo = c < lo ? c : lo;

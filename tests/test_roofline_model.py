@@ -27,3 +27,20 @@ def test_mi355x_model_for_the_headline_layer():
     assert abs(b - 246e6) < 1e6
     t_valu = e * 30 / roofline.MI355X_FP32_VECTOR_FLOPS
     assert abs(t_valu - 819e-6) < 1e-6
+
+
+def test_bench_reads_its_traffic_figure_from_the_tracked_profile():
+    """bench.py takes roofline.traffic from a machine-readable line of the tracked rocprofv3 summary: the line must
+    parse, name the commit it was measured at, and only answer for the workload and kernel families it covers."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    total, src = bench.measured_traffic("c3", "backward_walk")
+    assert src["file"] == bench.TRAFFIC_FILE and len(src["source_commit"]) >= 7
+    assert total == src["read"] + src["written"] and 1e9 < total < 4e9
+    fwd, _ = bench.measured_traffic("c3", "forward_pairs")
+    assert 1e8 < fwd < 1e9
+    assert bench.measured_traffic("c3", "forward_lds") == (None, None)       # a kernel family the summary does not cover
+    assert bench.measured_traffic("c4", "backward_walk") == (None, None)     # another workload
+    assert set(bench.KERNEL_ROLE.values()) <= set(bench.ROLE_SHARE)
